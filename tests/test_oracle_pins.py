@@ -1,0 +1,312 @@
+"""Pins for the fp64 oracle: everything here checks the oracle against something other than
+itself (hand-worked fixture, closed forms, textbook routines, brute force, invariants).
+CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from helpers import dense_softmax_attention, multiset_attention, multiplicity_matrix
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_index_fixture():
+    cases, cur = [], None
+    for line in open(os.path.join(GOLDEN, "index_map_eq1.txt")):
+        line = line.strip()
+        if line.startswith("# N ="):
+            parts = line[1:].replace(",", " ").split()
+            vals = {parts[i]: int(parts[i + 2]) for i in range(len(parts) - 2) if parts[i + 1] == "="}
+            cur = dict(N=vals["N"], w=vals["w"], r=vals["r"], rows={})
+            cases.append(cur)
+        elif line.startswith("# Kept") :
+            cur = dict(N=16, w=8, r=2, rows={})
+            cases.append(cur)
+        elif line and not line.startswith("#"):
+            h, rest = line.split(":")
+            cur["rows"][int(h)] = [int(t) for t in rest.replace("|", " ").split()]
+    return cases
+
+
+def test_index_map_matches_hand_worked_fixture(oracle):
+    cases = _read_index_fixture()
+    assert len(cases) == 2
+    for c in cases:
+        H = len(c["rows"])
+        idx = oracle.index_map(c["N"], H, c["w"], c["r"])
+        for h in range(H):
+            assert idx[h].tolist() == c["rows"][h]
+
+
+@pytest.mark.parametrize("N,w,r,H", [(64, 16, 4, 6), (4096, 2048, 2, 12), (256, 64, 2, 1), (48, 12, 3, 5), (32, 32, 1, 2)])
+def test_index_map_properties(oracle, N, w, r, H):
+    idx = oracle.index_map(N, H, w, r)
+    assert idx.shape == (H, N // r)
+    per = w // r
+    for h in range(H):
+        row = idx[h]
+        assert np.all(np.diff(row) > 0)                      # strictly increasing
+        assert np.all(row % r == h % r)                      # residue = head offset
+        seg = np.repeat(np.arange(N // w), per)
+        assert np.all((row >= seg * w) & (row < (seg + 1) * w))   # inside own segment
+        assert np.all(np.diff(row.reshape(-1, per), axis=1) == r)
+    if r == 1:
+        assert np.array_equal(idx, np.tile(np.arange(N, dtype=np.int32), (H, 1)))
+
+
+def test_index_map_explicit_offsets_and_errors(oracle):
+    idx = oracle.index_map(24, 2, 12, 3, head_offsets=[2, 0])
+    assert idx[0].tolist() == [2, 5, 8, 11, 14, 17, 20, 23]
+    assert idx[1].tolist() == [0, 3, 6, 9, 12, 15, 18, 21]
+    for bad in [(24, 2, 10, 2), (24, 2, 12, 5), (24, 2, 48, 1)]:
+        with pytest.raises(ValueError):
+            oracle.index_map(*bad)
+    with pytest.raises(ValueError):
+        oracle.index_map(24, 2, 12, 3, head_offsets=[3, 0])
+
+
+@pytest.mark.parametrize("scale", [0.125, 1.0])
+def test_w_equals_n_r1_is_dense_softmax_attention(oracle, scale):
+    rng = np.random.default_rng(11)
+    B, N, H, D = 2, 96, 3, 16
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out, lse = oracle.forward(q, k, v, [(N, 1)], scale)
+    for b in range(B):
+        for h in range(H):
+            o_ref, l_ref = dense_softmax_attention(q[b, :, h], k[b, :, h], v[b, :, h], scale)
+            np.testing.assert_allclose(out[b, :, h], o_ref, rtol=0, atol=1e-13)
+            np.testing.assert_allclose(lse[b, h], l_ref, rtol=0, atol=1e-12)
+
+
+def test_single_branch_equals_dense_attention_on_gathered_rows(oracle):
+    # each sparsified segment is a dense, independent problem (section 3.1, "Parallel processing")
+    rng = np.random.default_rng(5)
+    B, N, H, D, w, r = 1, 64, 4, 8, 16, 4
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out, lse = oracle.branch(q, k, v, w, r, 0.3)
+    for h in range(H):
+        covered = np.zeros(N, bool)
+        for i in range(N // w):
+            rows = i * w + (h % r) + r * np.arange(w // r)
+            covered[rows] = True
+            o_ref, l_ref = dense_softmax_attention(q[0, rows, h], k[0, rows, h], v[0, rows, h], 0.3)
+            np.testing.assert_allclose(out[0, rows, h], o_ref, atol=1e-13)
+            np.testing.assert_allclose(lse[0, h, rows], l_ref, atol=1e-12)
+        assert np.all(out[0, ~covered, h] == 0.0)            # O_init rows stay zero
+        assert np.all(np.isneginf(lse[0, h, ~covered]))
+
+
+def test_brute_force_all_small_divisor_combinations(oracle):
+    rng = np.random.default_rng(7)
+    B, N, H, D = 2, 32, 5, 4
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    singles = [(w, r) for w in (4, 8, 16, 32) for r in (1, 2, 4) if w % r == 0]
+    for br in singles:
+        out, lse = oracle.forward(q, k, v, [br], 0.5)
+        o_ref, l_ref = multiset_attention(q, k, v, 0.5, [br])
+        np.testing.assert_allclose(out, o_ref, atol=1e-12)
+        np.testing.assert_allclose(lse, l_ref, atol=1e-12)
+    for combo in itertools.combinations(singles, 3):
+        out, lse = oracle.forward(q, k, v, list(combo), 0.5)
+        o_ref, l_ref = multiset_attention(q, k, v, 0.5, list(combo))
+        np.testing.assert_allclose(out, o_ref, atol=1e-12)
+        np.testing.assert_allclose(lse, l_ref, atol=1e-12)
+
+
+def test_brute_force_non_power_of_two_and_explicit_offsets(oracle):
+    rng = np.random.default_rng(8)
+    B, N, H, D = 1, 36, 4, 3
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    branches = [(12, 3), (18, 2), (36, 6)]
+    offs = [[2, 0, 1, 2], [1, 1, 0, 0], [5, 3, 0, 4]]
+    out, lse = oracle.forward(q, k, v, branches, 1.0, head_offsets=offs)
+    o_ref, l_ref = multiset_attention(q, k, v, 1.0, branches, head_offsets=offs)
+    np.testing.assert_allclose(out, o_ref, atol=1e-12)
+    np.testing.assert_allclose(lse, l_ref, atol=1e-12)
+
+
+def test_forward_rows_matches_brute_force(oracle):
+    rng = np.random.default_rng(9)
+    B, N, H, D = 2, 64, 3, 8
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    branches = [(16, 1), (32, 2), (64, 4)]
+    bhn = np.array([(b, h, n) for b in range(B) for h in range(H) for n in range(N)], dtype=np.int32)
+    out_r, lse_r = oracle.forward_rows(q, k, v, branches, 0.35, bhn)
+    o_ref, l_ref = multiset_attention(q, k, v, 0.35, branches)
+    np.testing.assert_allclose(out_r, o_ref.transpose(0, 2, 1, 3).reshape(-1, D), atol=1e-12)
+    np.testing.assert_allclose(lse_r, l_ref.reshape(-1), atol=1e-12)
+
+
+def test_softmax_rows_sum_to_one_and_reproduce_output(oracle):
+    rng = np.random.default_rng(3)
+    B, N, H, D, w, r = 1, 48, 2, 8, 24, 2
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out, _ = oracle.branch(q, k, v, w, r, 0.7)
+    for h in range(H):
+        for seg in range(N // w):
+            p = oracle.segment_probs(q, k, v, w, r, 0.7, h % r, 0, h, seg)
+            assert p.shape == (w // r, w // r)
+            assert np.all(p > 0)
+            np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-14)
+            rows = seg * w + (h % r) + r * np.arange(w // r)
+            np.testing.assert_allclose(p @ v[0, rows, h], out[0, rows, h], atol=1e-13)
+
+
+def test_constant_v_gives_constant_rows(oracle):
+    rng = np.random.default_rng(4)
+    B, N, H, D = 1, 64, 3, 8
+    q, k = (rng.standard_normal((B, N, H, D)) for _ in range(2))
+    c = rng.standard_normal(D)
+    v = np.broadcast_to(c, (B, N, H, D)).copy()
+    out, lse = oracle.forward(q, k, v, [(16, 2), (64, 4)], 0.2)
+    covered = np.isfinite(lse).transpose(0, 2, 1)            # [B,N,H]
+    np.testing.assert_allclose(out[covered], np.broadcast_to(c, out[covered].shape), atol=1e-13)
+    assert np.all(out[~covered] == 0)
+
+
+def test_locality_tokens_outside_the_kept_set_do_not_matter(oracle):
+    rng = np.random.default_rng(6)
+    B, N, H, D, w, r = 1, 64, 2, 8, 32, 4
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out0, lse0 = oracle.branch(q, k, v, w, r, 0.4)
+    h, seg = 1, 1
+    rows = seg * w + (h % r) + r * np.arange(w // r)
+    other = np.setdiff1d(np.arange(N), rows)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for a in (q2, k2, v2):
+        a[0, other, h] += rng.standard_normal((len(other), D))
+    out1, lse1 = oracle.branch(q2, k2, v2, w, r, 0.4)
+    assert np.array_equal(out0[0, rows, h], out1[0, rows, h])    # bit for bit
+    assert np.array_equal(lse0[0, h, rows], lse1[0, h, rows])
+
+
+def test_key_shift_invariance(oracle):
+    rng = np.random.default_rng(12)
+    B, N, H, D = 1, 32, 2, 8
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    c = rng.standard_normal(D)
+    branches = [(8, 1), (32, 2)]
+    out0, lse0 = oracle.forward(q, k, v, branches, 0.5)
+    out1, lse1 = oracle.forward(q, k + c, v, branches, 0.5)
+    np.testing.assert_allclose(out1, out0, atol=1e-12)
+    shift = 0.5 * np.einsum("bnhd,d->bhn", q, c)
+    fin = np.isfinite(lse0)
+    np.testing.assert_allclose(lse1[fin], (lse0 + shift)[fin], atol=1e-12)
+
+
+def test_offset_symmetry_for_whole_sequence_segment(oracle):
+    # with w = N, keeping rows o, o+r, ... equals the offset-0 result on the sequence rolled by -o
+    rng = np.random.default_rng(13)
+    B, N, H, D, r, o = 1, 24, 1, 4, 3, 2
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out_o, lse_o = oracle.forward(q, k, v, [(N, r)], 0.6, head_offsets=[[o]])
+    roll = lambda a: np.roll(a, -o, axis=1)
+    out_0, lse_0 = oracle.forward(roll(q), roll(k), roll(v), [(N, r)], 0.6, head_offsets=[[0]])
+    np.testing.assert_array_equal(out_o, np.roll(out_0, o, axis=1))
+    np.testing.assert_array_equal(lse_o, np.roll(lse_0, o, axis=2))
+
+
+def _subset_attention(q, k, v, keys, scale):
+    return dense_softmax_attention(q, k[keys], v[keys], scale)
+
+
+def test_merge_of_disjoint_key_sets_is_attention_over_the_union(oracle):
+    rng = np.random.default_rng(21)
+    n, D, nk = 10, 6, 40
+    q, k, v = rng.standard_normal((n, D)), rng.standard_normal((nk, D)), rng.standard_normal((nk, D))
+    perm = rng.permutation(nk)
+    sets = [perm[:7], perm[7:20], perm[20:36]]
+    parts = [_subset_attention(q, k, v, s, 0.45) for s in sets]
+    out, lse = oracle.merge(np.stack([p[0] for p in parts]), np.stack([p[1] for p in parts]))
+    o_ref, l_ref = _subset_attention(q, k, v, np.concatenate(sets), 0.45)
+    np.testing.assert_allclose(out, o_ref, atol=1e-13)
+    np.testing.assert_allclose(lse, l_ref, atol=1e-13)
+
+
+def test_merge_overlap_is_multiset_union_self_merge_adds_ln2_and_order_is_irrelevant(oracle):
+    rng = np.random.default_rng(22)
+    n, D, nk = 8, 5, 30
+    q, k, v = rng.standard_normal((n, D)), rng.standard_normal((nk, D)), rng.standard_normal((nk, D))
+    a, b = np.arange(0, 18), np.arange(10, 30)                # overlap 10..17
+    pa, pb = _subset_attention(q, k, v, a, 0.8), _subset_attention(q, k, v, b, 0.8)
+    out, lse = oracle.merge(np.stack([pa[0], pb[0]]), np.stack([pa[1], pb[1]]))
+    o_ref, l_ref = _subset_attention(q, k, v, np.concatenate([a, b]), 0.8)   # duplicates count twice
+    np.testing.assert_allclose(out, o_ref, atol=1e-13)
+    np.testing.assert_allclose(lse, l_ref, atol=1e-13)
+    out2, lse2 = oracle.merge(np.stack([pb[0], pa[0]]), np.stack([pb[1], pa[1]]))
+    np.testing.assert_allclose(out2, out, atol=1e-15)
+    np.testing.assert_allclose(lse2, lse, atol=1e-15)
+    out3, lse3 = oracle.merge(np.stack([pa[0], pa[0]]), np.stack([pa[1], pa[1]]))
+    np.testing.assert_allclose(out3, pa[0], atol=1e-14)
+    np.testing.assert_allclose(lse3, pa[1] + np.log(2.0), atol=1e-14)
+
+
+def test_merge_ignores_absent_branches_and_handles_uncovered_rows(oracle):
+    ob = np.array([[[1.0, 2.0]], [[5.0, 6.0]], [[0.0, 0.0]]])
+    lb = np.array([[0.3], [-np.inf], [-np.inf]])
+    out, lse = oracle.merge(ob, lb)
+    np.testing.assert_allclose(out, [[1.0, 2.0]], atol=1e-15)
+    np.testing.assert_allclose(lse, [0.3], atol=1e-15)
+    out, lse = oracle.merge(np.zeros((2, 1, 2)), np.full((2, 1), -np.inf))
+    assert np.all(out == 0) and np.all(np.isneginf(lse))
+
+
+@pytest.mark.parametrize("name", ["tiny", "sam", "highres"])
+def test_zero_query_closed_form_on_the_workload_shapes(oracle, name):
+    """q = 0: every kept key has weight exp(0), so lse = ln(#keys with multiplicity) and out is the
+    multiplicity-weighted mean of V.  Row classes at the workload shapes: 1024*{1,2,3} keys for the
+    4096-token configs, 2048*{1,2,3,4} for the 16384-token one, 32 or none for the tiny one."""
+    from paper_2403_09195_amd import synth
+    cfg = synth.CONFIGS[name]
+    B, H, N, D, branches = 1, cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
+    rng = np.random.default_rng(31)
+    q = np.zeros((B, N, H, D))
+    k = rng.standard_normal((B, N, H, D))
+    v = rng.standard_normal((B, N, H, D))
+    picks = rng.integers(0, N, size=24)
+    bhn = np.array([(0, h, n) for h in range(H) for n in picks], dtype=np.int32)
+    out, lse = oracle.forward_rows(q, k, v, branches, 0.125, bhn)
+    per_seg = branches[0][0] // branches[0][1]
+    seen = set()
+    for row, (_, h, n) in enumerate(bhn):
+        mult = np.zeros(N)
+        for (w, r) in branches:
+            if n % r == h % r:
+                j = np.arange(N)
+                mult += ((j // w) == (n // w)) & (j % r == h % r)
+        tot = mult.sum()
+        if tot == 0:
+            assert np.isneginf(lse[row]) and np.all(out[row] == 0)
+            seen.add(0)
+            continue
+        assert tot % per_seg == 0
+        seen.add(int(tot // per_seg))
+        np.testing.assert_allclose(lse[row], np.log(tot), atol=1e-12)
+        np.testing.assert_allclose(out[row], (mult @ v[0, :, h]) / tot, atol=1e-12)
+    expect = {"tiny": {0, 1}, "sam": {1, 2, 3}, "highres": {1, 2, 3, 4}}[name]
+    assert seen == expect
+
+
+def test_row_class_sizes_at_workload_shapes():
+    # 4096-token configs: per head 2048 / 1024 / 1024 rows in 1 / 2 / 3 branches
+    m = multiplicity_matrix(4096, 5, [(1024, 1), (2048, 2), (4096, 4)])
+    keys = m.sum(axis=1)
+    assert sorted(np.unique(keys).tolist()) == [1024, 2048, 3072]
+    assert [(keys == c).sum() for c in (1024, 2048, 3072)] == [2048, 1024, 1024]
+    assert m.sum() == 7 * 1024 * 1024
+
+
+def test_small_full_forward_consistent_with_rows_and_scale_one(oracle):
+    rng = np.random.default_rng(41)
+    B, N, H, D = 1, 128, 4, 16
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    branches = [(32, 1), (64, 2), (128, 4)]
+    out, lse, bo, bl = oracle.forward(q, k, v, branches, 1.0, return_branches=True)
+    o_ref, l_ref = multiset_attention(q, k, v, 1.0, branches)
+    np.testing.assert_allclose(out, o_ref, atol=1e-12)
+    np.testing.assert_allclose(lse, l_ref, atol=1e-12)
+    for x, (w, r) in enumerate(branches):
+        ob, lb = oracle.branch(q, k, v, w, r, 1.0)
+        assert np.array_equal(ob, bo[x]) and np.array_equal(lb, bl[x])
