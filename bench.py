@@ -1,0 +1,116 @@
+#!/usr/bin/env python3
+"""Benchmark of the dilated flash attention forward on one MI355X.
+
+A step is one pass of the whole hot path (gather + attention + placement + branch merge,
+one dfa_forward call) over one synthetic batch of the throughput workload: B = 16 images of
+64x64 = 4096 tokens, 12 heads x 64, bf16, branches (1024,1), (2048,2), (4096,4).
+Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
+WORKLOAD = "throughput"
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=WORKLOAD, help="name in synth.CONFIGS (default: throughput)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs: "
+                 "(b, h) units are independent, so N GPUs would each run this same kernel on B/N images). "
+                 "Run with --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2403_09195_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.lib()
+    torch.cuda.set_device(0)
+
+    cfg = synth.CONFIGS[args.workload]
+    Bsz, H, N, D, branches = cfg["B"], cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
+    scale = 1.0 / (D ** 0.5)
+    storage, exact = synth.qkv(cfg["seed"], Bsz, N, H, D, cfg["dtype"])
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    q, k, v = (dev(a) for a in storage)
+    out = torch.empty((Bsz, N, H, D), dtype=q.dtype, device="cuda")
+    lse = torch.empty((Bsz, H, N), dtype=torch.float32, device="cuda")
+    flops = synth.useful_flops(Bsz, H, N, D, branches)
+
+    for _ in range(args.warmup):
+        binding.forward(q, k, v, branches, scale, out=out, lse=lse)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        binding.forward(q, k, v, branches, scale, out=out, lse=lse)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    tflops = flops / (wall / args.steps) / 1e12
+
+    # dominant (only) kernel: mean launch duration from HIP events on the launch stream
+    kern_ms = binding.forward_timed(q, k, v, branches, scale, args.steps, out=out, lse=lse)
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+
+    # sampled parity against the oracle (cheap sanity check of what was just timed)
+    from oracle import dfa_oracle
+    rng = np.random.default_rng(1)
+    ns = 96
+    bhn = np.stack([rng.integers(0, Bsz, ns), rng.integers(0, H, ns), rng.integers(0, N, ns)], axis=1).astype(np.int32)
+    o_ref, l_ref = dfa_oracle.forward_rows(*exact, branches, scale, bhn)
+    got = out.float().cpu().numpy().astype(np.float64)[bhn[:, 0], bhn[:, 2], bhn[:, 1]]
+    max_err = float(np.abs(got - o_ref).max())
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        bs = min(Bsz, 8)
+        sub = tuple(np.ascontiguousarray(a[:bs]) for a in exact)
+        t0 = time.perf_counter()
+        dfa_oracle.forward(*sub, branches, scale)
+        dt = time.perf_counter() - t0
+        cpu = {"value": synth.useful_flops(bs, H, N, D, branches) / dt / 1e12, "unit": "TFLOP/s",
+               "cores": dfa_oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
+               "sample": f"first {bs} of {Bsz} images, all {H} heads ({bs * H} of {Bsz * H} independent (b,h) units), fp64"}
+
+    line = {
+        "metric": "dilated-attention TFLOP/s (useful attention FLOPs, 4*D per kept query-key pair)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={Bsz} H={H} N={N} D={D} branches={branches} offset=h mod r scale=1/sqrt(D)"},
+        "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+        "us_per_image_per_layer": ms_per_step * 1e3 / Bsz,
+        "us_per_image_12_layers_attention_only": 12 * ms_per_step * 1e3 / Bsz,
+        "useful_flops_per_step": flops,
+        "sampled_max_abs_err_vs_oracle": max_err,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "dfa_fwd_bf16_kernel", "kernel_ms": kern_ms},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,175 @@
+/*
+ * dfa.h - C ABI of the MI355X (gfx950) Dilated Flash Attention forward library.
+ *
+ * The operation is the attention operator of SAM-Lightening, section 3.1:
+ *   - Segmentation + sparsification (Eq. 1): the N tokens of one image are cut into N/w
+ *     segments of length w; inside segment i the rows i*w + o + j*r (j = 0 .. w/r-1) of
+ *     Q, K and V are kept.  The paper writes o = 0; here o depends on the head
+ *     (o = h mod r by default, or an explicit per-head table).
+ *   - Per-segment attention (Eq. 2): softmax(scale * Q~_i K~_i^T) V~_i over the kept rows.
+ *     Eq. 2 prints no scale factor: pass scale = 1.0f for the literal equation,
+ *     1/sqrt(D) for the usual flash-attention convention.
+ *   - Recomposition (Eq. 3): results are placed at the token positions they were taken
+ *     from in a zero matrix of the input's shape; rows that nothing keeps are 0.
+ *   - Several (w, r) branches are merged with their log-sum-exp weights:
+ *     L = log sum_b exp(lse_b), out = sum_b exp(lse_b - L) * out_b over the branches that
+ *     keep the row (the paper treats a single branch; nb = 1 reproduces it).
+ *
+ * Conventions shared by all entry points
+ *   - Pointers marked "device" are device memory of the current HIP device, "host" are
+ *     ordinary host memory read before the call returns.  The caller owns every buffer.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and the call returns without synchronising, unless stated otherwise.
+ *   - Tensors q, k, v are addressed as base + b*stride.b + n*stride.n + h*stride.h + d
+ *     (strides in elements, the D elements of one row contiguous).  Every row must start
+ *     on a 16-byte boundary.  Outputs are contiguous: out [B, N, H, D], lse [B, H, N].
+ *   - D must be 64.  Non-causal, no mask, no bias.
+ *   - Return value: DFA_OK (0) or a negative dfa_status_t.  Argument errors are found on
+ *     the host before anything is enqueued.  No C++ exception crosses this boundary.
+ *   - dfa_forward / dfa_forward_branch keep a small per-process cache of launch plans
+ *     (tile lists in device memory, a few hundred KB each), keyed by device and problem
+ *     shape.  The first call with a new shape allocates and uploads its plan
+ *     (synchronously); later calls with that shape allocate nothing.
+ *     dfa_release_plans() frees them.
+ */
+#ifndef DFA_H
+#define DFA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DFA_MAX_BRANCHES 8
+#define DFA_HEAD_DIM 64
+
+typedef enum {
+    DFA_OK = 0,
+    DFA_ERR_NULL = -1,      /* a required pointer is NULL                                    */
+    DFA_ERR_SHAPE = -2,     /* B, H, N <= 0; D != 64; w > N; N % w != 0; w % r != 0; r < 1;  */
+                            /* head offset outside [0, r); scale not finite or <= 0          */
+    DFA_ERR_BRANCHES = -3,  /* nb < 1 or nb > DFA_MAX_BRANCHES                               */
+    DFA_ERR_DTYPE = -4,     /* unknown dfa_dtype_t                                           */
+    DFA_ERR_ALIGN = -5,     /* a base pointer or stride breaks the 16-byte row alignment     */
+    DFA_ERR_LAUNCH = -6,    /* the HIP runtime refused an allocation, copy or launch         */
+    DFA_ERR_TOO_LARGE = -7  /* index arithmetic would overflow the kernel's 32-bit counters  */
+} dfa_status_t;
+
+typedef enum { DFA_BF16 = 0, DFA_F32 = 1 } dfa_dtype_t;
+
+/* One (segment length, sparsification interval) pair of section 3.1. */
+typedef struct { int32_t w; int32_t r; } dfa_branch_t;
+
+/* Element strides of a [B, N, H, D]-addressed tensor; D is contiguous. */
+typedef struct { int64_t b; int64_t n; int64_t h; } dfa_strides_t;
+
+int dfa_version(void);
+const char *dfa_error_string(int code);
+
+/*
+ * Kept-row indexer, host (Eq. 1 with the per-head start).
+ * out_idx (host, int32 [H][N/r]): out_idx[h][i*(w/r) + j] = i*w + o_h + j*r.
+ * head_offsets (host, int32 [H]) or NULL for o_h = h mod r.  Uses no GPU.
+ */
+int dfa_index_map(int32_t N, int32_t H, dfa_branch_t br, const int32_t *head_offsets,
+                  int32_t *out_idx);
+
+/*
+ * The same map computed by the device indexer (the routine the gather, scatter and
+ * attention kernels address kept rows with), written to d_out_idx (device, int32
+ * [H][N/r]).  head_offsets is host memory or NULL.  Asynchronous on `stream`.
+ */
+int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t *head_offsets,
+                         int32_t *d_out_idx, void *stream);
+
+/*
+ * Main entry: gather (Eq. 1) + per-segment attention (Eq. 2) + placement (Eq. 3) +
+ * log-sum-exp merge of the nb branches, in one fused kernel.
+ *   q, k, v       device, dtype dt, strided as described above
+ *   branches      host, nb entries; head_offsets host int32 [nb][H] or NULL (o = h mod r)
+ *   out           device, dtype dt, contiguous [B, N, H, D]; rows kept by no branch get 0
+ *   lse           device, fp32 contiguous [B, H, N], natural log of the sum of
+ *                 exp(scale * q.k) over the row's keys (each key counted once per branch
+ *                 that pairs it with the row); -inf for rows kept by no branch.  May be NULL.
+ * dt = DFA_BF16: bf16 operands on the matrix cores, fp32 accumulation and softmax
+ * statistics, probabilities rounded to bf16 before the product with V, result rounded to
+ * bf16.  dt = DFA_F32: fp32 throughout.
+ */
+int dfa_forward(const void *q, const void *k, const void *v,
+                dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
+                void *out, float *lse, void *stream);
+
+/*
+ * One branch, unmerged (Eq. 1-3 for a single (w, r)): out_b device fp32 [B, N, H, D]
+ * (0 on rows the branch does not keep), lse_b device fp32 [B, H, N] (-inf there).
+ * head_offsets host int32 [H] or NULL.  Inputs of dtype dt as in dfa_forward.
+ */
+int dfa_forward_branch(const void *q, const void *k, const void *v,
+                       dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                       int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                       dfa_branch_t br, const int32_t *head_offsets,
+                       float *out_b, float *lse_b, void *stream);
+
+/*
+ * Stand-alone log-sum-exp merge of nb unmerged branch results.
+ *   out_b device fp32 [nb][B, N, H, D], lse_b device fp32 [nb][B, H, N]
+ *   out   device dtype dt [B, N, H, D], lse device fp32 [B, H, N] (may be NULL)
+ */
+int dfa_merge(const float *out_b, const float *lse_b, int32_t nb,
+              int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+              void *out, float *lse, void *stream);
+
+/*
+ * Stand-alone gather (Eq. 1): kept rows of one strided tensor x into a dense
+ * xg (device, dtype dt, contiguous [B, H, N/r, D]), rows in index-map order.
+ */
+int dfa_gather(const void *x, dfa_strides_t sx, int32_t B, int32_t H, int32_t N, int32_t D,
+               dfa_dtype_t dt, dfa_branch_t br, const int32_t *head_offsets,
+               void *xg, void *stream);
+
+/*
+ * Stand-alone placement (the MAP of Eq. 3): dense og (device, dtype dt, [B, H, N/r, D])
+ * back to token positions in out (device, dtype dt, contiguous [B, N, H, D]); rows the
+ * branch does not keep are written as 0, so out needs no initialisation.
+ */
+int dfa_scatter(const void *og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                dfa_branch_t br, const int32_t *head_offsets, void *out, void *stream);
+
+/*
+ * Host-side view of the launch plan dfa_forward would use (no GPU needed): the query
+ * rows of each head are grouped by the set of (branch, segment) pairs that keep them and
+ * cut into tiles; every tile carries one arithmetic key progression per member branch.
+ * Pass NULL arrays to query the sizes only.
+ *   n_tiles, n_rows, n_segs, n_items   out, host: entry counts
+ *   tiles  host int32 [n_tiles][6] = (h, row_begin, nrows, seg_begin, nseg, unused)
+ *   rows   host int32 [n_rows]     token positions, tile after tile
+ *   segs   host int32 [n_segs][3]  = (first key, key stride, key count)
+ *   items  host int32 [n_items][2] = (tile or -1 for padding, b) in launch order
+ */
+int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branches, int32_t nb,
+                      const int32_t *head_offsets, int32_t *n_tiles, int32_t *n_rows,
+                      int32_t *n_segs, int32_t *n_items, int32_t *tiles, int32_t *rows,
+                      int32_t *segs, int32_t *items);
+
+/* Frees every cached launch plan of every device.  Synchronises the devices involved. */
+int dfa_release_plans(void);
+
+/*
+ * Times `iters` back-to-back dfa_forward launches with HIP events recorded on `stream`
+ * (the stream the kernel runs on) and returns the mean milliseconds per launch in *ms.
+ * Arguments as dfa_forward.  Synchronises `stream`.  For benchmarks.
+ */
+int dfa_forward_timed(const void *q, const void *k, const void *v,
+                      dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                      int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                      const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
+                      void *out, float *lse, void *stream, int32_t iters, float *ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFA_H */

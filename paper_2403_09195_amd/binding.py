@@ -1,0 +1,258 @@
+"""ctypes binding of libdfa.so: same names as the C ABI in include/dfa.h.
+
+Argument marshalling only.  Tensors are torch tensors on the GPU (torch is used for
+device memory and streams); data pointers, element strides and the current HIP stream are
+passed to the library, which runs every step of the path in its own kernels.  There is no
+fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from .build import LIB_PATH
+
+DFA_BF16, DFA_F32 = 0, 1
+DFA_MAX_BRANCHES = 8
+
+EXPORTS = [
+    "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_forward",
+    "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
+    "dfa_release_plans", "dfa_forward_timed",
+]
+
+
+class Branch(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_int32), ("r", ctypes.c_int32)]
+
+
+class Strides(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int64), ("n", ctypes.c_int64), ("h", ctypes.c_int64)]
+
+
+class DfaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {error_string(code)} (code {code})")
+
+
+_lib = None
+_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+def lib():
+    """Loads libdfa.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        import torch  # noqa: F401  (brings in libamdhip64 first)
+        L = ctypes.CDLL(LIB_PATH)
+        L.dfa_error_string.restype = ctypes.c_char_p
+        L.dfa_error_string.argtypes = [ctypes.c_int]
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+        L.dfa_index_map.argtypes = [i32, i32, Branch, _i32p, _i32p]
+        L.dfa_index_map_device.argtypes = [i32, i32, Branch, _i32p, vp, vp]
+        fwd = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, ctypes.c_int, f32,
+               ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp]
+        L.dfa_forward.argtypes = fwd
+        L.dfa_forward_timed.argtypes = fwd + [i32, ctypes.POINTER(f32)]
+        L.dfa_forward_branch.argtypes = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32,
+                                         ctypes.c_int, f32, Branch, _i32p, vp, vp, vp]
+        L.dfa_merge.argtypes = [vp, vp, i32, i32, i32, i32, i32, ctypes.c_int, vp, vp, vp]
+        L.dfa_gather.argtypes = [vp, Strides, i32, i32, i32, i32, ctypes.c_int, Branch, _i32p, vp, vp]
+        L.dfa_scatter.argtypes = [vp, i32, i32, i32, i32, ctypes.c_int, Branch, _i32p, vp, vp]
+        L.dfa_plan_describe.argtypes = [i32, i32, i32, ctypes.POINTER(Branch), i32, _i32p,
+                                        _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p]
+        for name in EXPORTS:
+            if name != "dfa_error_string":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def error_string(code: int) -> str:
+    return lib().dfa_error_string(int(code)).decode()
+
+
+def version() -> int:
+    return lib().dfa_version()
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise DfaError(rc, where)
+
+
+def _branches(branches):
+    arr = (Branch * len(branches))(*[Branch(int(w), int(r)) for (w, r) in branches])
+    return arr, len(branches)
+
+
+def _i32_array(values):
+    """Flattens nested ints into a C int32 array; None -> NULL."""
+    if values is None:
+        return None
+    flat = []
+    for row in values:
+        if isinstance(row, (list, tuple)) or hasattr(row, "__iter__"):
+            flat.extend(int(x) for x in row)
+        else:
+            flat.append(int(row))
+    return (ctypes.c_int32 * len(flat))(*flat)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return DFA_BF16
+    if t.dtype == torch.float32:
+        return DFA_F32
+    raise DfaError(-4, "dtype")
+
+
+def _strides(t):
+    """Element strides (b, n, h) of a [B, N, H, D] view whose last dim is contiguous."""
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise DfaError(-5, "tensor must be [B, N, H, D] with contiguous D")
+    return Strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _gpu(t, name):
+    if not t.is_cuda:
+        raise RuntimeError(f"{name} must live in GPU memory")
+
+
+def index_map(N, H, w, r, head_offsets=None):
+    """Host indexer: list of H lists with the kept token positions of one branch (Eq. 1)."""
+    out = (ctypes.c_int32 * (H * (N // max(r, 1))))()
+    _check(lib().dfa_index_map(N, H, Branch(w, r), _i32_array(head_offsets), out), "dfa_index_map")
+    per = N // r
+    return [list(out[h * per:(h + 1) * per]) for h in range(H)]
+
+
+def index_map_device(N, H, w, r, head_offsets=None):
+    """Device indexer: int32 tensor [H, N // r] on the GPU."""
+    import torch
+    out = torch.empty((H, N // r), dtype=torch.int32, device="cuda")
+    _check(lib().dfa_index_map_device(N, H, Branch(w, r), _i32_array(head_offsets),
+                                      ctypes.c_void_p(out.data_ptr()), _stream()), "dfa_index_map_device")
+    return out
+
+
+def _fwd_args(q, k, v, branches, scale, head_offsets, out, lse):
+    for t, nm in ((q, "q"), (k, "k"), (v, "v"), (out, "out")):
+        _gpu(t, nm)
+    B, N, H, D = q.shape
+    br, nb = _branches(branches)
+    return [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+            _strides(q), _strides(k), _strides(v), B, H, N, D, _dtype_code(q), ctypes.c_float(scale),
+            br, nb, _i32_array(head_offsets), ctypes.c_void_p(out.data_ptr()),
+            ctypes.c_void_p(lse.data_ptr() if lse is not None else None), _stream()]
+
+
+def forward(q, k, v, branches, scale, head_offsets=None, out=None, lse=None, want_lse=True):
+    """Fused dilated attention.  q, k, v [B, N, H, D] (may be strided views) -> (out, lse)."""
+    import torch
+    B, N, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=q.dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    _check(lib().dfa_forward(*_fwd_args(q, k, v, branches, scale, head_offsets, out, lse)), "dfa_forward")
+    return out, lse
+
+
+def forward_timed(q, k, v, branches, scale, iters, head_offsets=None, out=None, lse=None):
+    """Mean milliseconds per dfa_forward launch over `iters` launches (HIP events on the stream)."""
+    import torch
+    B, N, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    ms = ctypes.c_float(0.0)
+    args = _fwd_args(q, k, v, branches, scale, head_offsets, out, lse) + [int(iters), ctypes.byref(ms)]
+    _check(lib().dfa_forward_timed(*args), "dfa_forward_timed")
+    return ms.value
+
+
+def forward_branch(q, k, v, w, r, scale, head_offsets=None):
+    """One unmerged branch: (out_b fp32 [B,N,H,D] zero on rows not kept, lse_b fp32 [B,H,N] -inf there)."""
+    import torch
+    for t, nm in ((q, "q"), (k, "k"), (v, "v")):
+        _gpu(t, nm)
+    B, N, H, D = q.shape
+    out_b = torch.empty((B, N, H, D), dtype=torch.float32, device=q.device)
+    lse_b = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    _check(lib().dfa_forward_branch(
+        ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+        _strides(q), _strides(k), _strides(v), B, H, N, D, _dtype_code(q), ctypes.c_float(scale),
+        Branch(w, r), _i32_array(head_offsets), ctypes.c_void_p(out_b.data_ptr()),
+        ctypes.c_void_p(lse_b.data_ptr()), _stream()), "dfa_forward_branch")
+    return out_b, lse_b
+
+
+def merge(out_b, lse_b, dtype):
+    """LSE merge of stacked branch results: out_b fp32 [nb,B,N,H,D], lse_b fp32 [nb,B,H,N]."""
+    import torch
+    _gpu(out_b, "out_b")
+    _gpu(lse_b, "lse_b")
+    nb, B, N, H, D = out_b.shape
+    out = torch.empty((B, N, H, D), dtype=dtype, device=out_b.device)
+    lse = torch.empty((B, H, N), dtype=torch.float32, device=out_b.device)
+    code = DFA_BF16 if dtype == torch.bfloat16 else DFA_F32
+    _check(lib().dfa_merge(ctypes.c_void_p(out_b.data_ptr()), ctypes.c_void_p(lse_b.data_ptr()), nb, B, H, N, D,
+                           code, ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()), _stream()),
+           "dfa_merge")
+    return out, lse
+
+
+def gather(x, w, r, head_offsets=None):
+    """Kept rows of x [B, N, H, D] -> dense [B, H, N // r, D] (Eq. 1)."""
+    import torch
+    _gpu(x, "x")
+    B, N, H, D = x.shape
+    xg = torch.empty((B, H, N // r, D), dtype=x.dtype, device=x.device)
+    _check(lib().dfa_gather(ctypes.c_void_p(x.data_ptr()), _strides(x), B, H, N, D, _dtype_code(x), Branch(w, r),
+                            _i32_array(head_offsets), ctypes.c_void_p(xg.data_ptr()), _stream()), "dfa_gather")
+    return xg
+
+
+def scatter(og, N, w, r, head_offsets=None):
+    """Dense [B, H, N // r, D] back to token positions [B, N, H, D], zero elsewhere (Eq. 3)."""
+    import torch
+    _gpu(og, "og")
+    B, H, _, D = og.shape
+    out = torch.empty((B, N, H, D), dtype=og.dtype, device=og.device)
+    _check(lib().dfa_scatter(ctypes.c_void_p(og.data_ptr()), B, H, N, D, _dtype_code(og), Branch(w, r),
+                             _i32_array(head_offsets), ctypes.c_void_p(out.data_ptr()), _stream()), "dfa_scatter")
+    return out
+
+
+def plan_describe(B, H, N, branches, head_offsets=None):
+    """Host view of the launch plan: dict of numpy int32 arrays (tiles, rows, segs, items)."""
+    import numpy as np
+    br, nb = _branches(branches)
+    off = _i32_array(head_offsets)
+    cnt = [ctypes.c_int32(0) for _ in range(4)]
+    refs = [ctypes.byref(c) for c in cnt]
+    _check(lib().dfa_plan_describe(B, H, N, br, nb, off, *refs, None, None, None, None), "dfa_plan_describe")
+    nt, nr, ns, ni = (c.value for c in cnt)
+    tiles = np.zeros((nt, 6), dtype=np.int32)
+    rows = np.zeros((nr,), dtype=np.int32)
+    segs = np.zeros((max(ns, 1), 3), dtype=np.int32)
+    items = np.zeros((ni, 2), dtype=np.int32)
+    p = lambda a: a.ctypes.data_as(_i32p)
+    _check(lib().dfa_plan_describe(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(items)),
+           "dfa_plan_describe")
+    return dict(tiles=tiles, rows=rows, segs=segs[:ns], items=items)
+
+
+def release_plans():
+    _check(lib().dfa_release_plans(), "dfa_release_plans")

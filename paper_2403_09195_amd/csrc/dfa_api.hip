@@ -1,0 +1,339 @@
+// C ABI of the dilated flash attention library: argument checks, launch-plan cache, launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/dfa.h"
+#include "dfa_device.h"
+#include "dfa_plan.h"
+
+namespace {
+
+using namespace dfa;
+
+struct DevicePlan {
+    void* base = nullptr;
+    const Tile* tiles = nullptr;
+    const int32_t* rows = nullptr;
+    const KeySeg* segs = nullptr;
+    const Item* items = nullptr;
+    int32_t n_items = 0;
+    int device = 0;
+};
+
+std::mutex g_mu;
+std::map<std::vector<int32_t>, DevicePlan> g_plans;
+
+int plan_order_mode() {
+    // measurement knob, read when a plan is built: DFA_PLAN_ORDER = 0, 1 or 2 (default)
+    const char* e = std::getenv("DFA_PLAN_ORDER");
+    if (e && e[0] >= '0' && e[0] <= '2' && e[1] == 0) return e[0] - '0';
+    return 2;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Looks the plan up, building and uploading it on first use.  Holds g_mu.
+int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+             const int32_t* offsets, DevicePlan* out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return DFA_ERR_LAUNCH;
+    const int mode = plan_order_mode();
+    std::vector<int32_t> key = {device, B, H, N, nb, mode, offsets ? 1 : 0};
+    for (int x = 0; x < nb; ++x) {
+        key.push_back(br[x].w);
+        key.push_back(br[x].r);
+    }
+    if (offsets) key.insert(key.end(), offsets, offsets + (size_t)nb * H);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto it = g_plans.find(key);
+    if (it != g_plans.end()) {
+        *out = it->second;
+        return DFA_OK;
+    }
+    HostPlan hp;
+    build_plan(B, H, N, br, nb, offsets, mode, &hp);
+    if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
+    const size_t b_tiles = align256(hp.tiles.size() * sizeof(Tile));
+    const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
+    const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
+    const size_t b_items = align256(hp.items.size() * sizeof(Item));
+    DevicePlan dp;
+    dp.device = device;
+    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items) != hipSuccess) return DFA_ERR_LAUNCH;
+    char* base = static_cast<char*>(dp.base);
+    bool ok = true;
+    ok = ok && hipMemcpy(base, hp.tiles.data(), hp.tiles.size() * sizeof(Tile), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(base + b_tiles, hp.rows.data(), hp.rows.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    if (!hp.segs.empty())
+        ok = ok && hipMemcpy(base + b_tiles + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(base + b_tiles + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+        (void)hipFree(dp.base);
+        return DFA_ERR_LAUNCH;
+    }
+    dp.tiles = reinterpret_cast<const Tile*>(base);
+    dp.rows = reinterpret_cast<const int32_t*>(base + b_tiles);
+    dp.segs = reinterpret_cast<const KeySeg*>(base + b_tiles + b_rows);
+    dp.items = reinterpret_cast<const Item*>(base + b_tiles + b_rows + b_segs);
+    dp.n_items = (int32_t)hp.items.size();
+    g_plans[key] = dp;
+    *out = dp;
+    return DFA_OK;
+}
+
+int elem_size(dfa_dtype_t dt) { return dt == DFA_BF16 ? 2 : 4; }
+
+bool aligned_rows(const void* p, dfa_strides_t s, int esize) {
+    if (reinterpret_cast<uintptr_t>(p) % 16) return false;
+    return (s.b * esize) % 16 == 0 && (s.n * esize) % 16 == 0 && (s.h * esize) % 16 == 0;
+}
+
+int check_common(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt) {
+    if (B <= 0 || H <= 0 || N <= 0 || D != DFA_HEAD_DIM) return DFA_ERR_SHAPE;
+    if (dt != DFA_BF16 && dt != DFA_F32) return DFA_ERR_DTYPE;
+    if ((int64_t)B * H * N > ((int64_t)1 << 40)) return DFA_ERR_TOO_LARGE;
+    return DFA_OK;
+}
+
+int make_offsets(const int32_t* head_offsets, int32_t H, int32_t r, HeadOffsets* o) {
+    std::memset(o, 0, sizeof(*o));
+    if (!head_offsets) return DFA_OK;
+    if (H > kMaxExplicitHeads) return DFA_ERR_TOO_LARGE;
+    o->explicit_table = 1;
+    for (int h = 0; h < H; ++h) {
+        if (head_offsets[h] < 0 || head_offsets[h] >= r) return DFA_ERR_SHAPE;
+        o->o[h] = head_offsets[h];
+    }
+    return DFA_OK;
+}
+
+int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                 dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                 float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                 void* out, bool out_f32, float* lse, void* stream) {
+    if (!q || !k || !v || !out) return DFA_ERR_NULL;
+    int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    rc = check_branches(H, N, branches, nb, head_offsets);
+    if (rc != DFA_OK) return rc;
+    if (!std::isfinite(scale) || scale <= 0.f) return DFA_ERR_SHAPE;
+    const int es = elem_size(dt);
+    if (!aligned_rows(q, sq, es) || !aligned_rows(k, sk, es) || !aligned_rows(v, sv, es)) return DFA_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(out) % 16 || (lse && reinterpret_cast<uintptr_t>(lse) % 4)) return DFA_ERR_ALIGN;
+
+    DevicePlan dp;
+    rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+    if (rc != DFA_OK) return rc;
+
+    FwdParams p;
+    p.q = q; p.k = k; p.v = v;
+    p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
+    p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
+    p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
+    p.out = out; p.lse = lse;
+    p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
+    p.H = H; p.N = N; p.scale = scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (dt == DFA_BF16) e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
+    else e = launch_fwd_f32(p, dp.n_items, st);        // fp32 inputs always give fp32 output
+    return e == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dfa_version(void) { return 100; }
+
+const char* dfa_error_string(int code) {
+    switch (code) {
+        case DFA_OK: return "ok";
+        case DFA_ERR_NULL: return "a required pointer is NULL";
+        case DFA_ERR_SHAPE: return "bad shape, branch (w, r), head offset or scale";
+        case DFA_ERR_BRANCHES: return "number of branches outside 1..DFA_MAX_BRANCHES";
+        case DFA_ERR_DTYPE: return "unknown dtype";
+        case DFA_ERR_ALIGN: return "pointer or stride breaks 16-byte row alignment";
+        case DFA_ERR_LAUNCH: return "HIP runtime error (allocation, copy or launch)";
+        case DFA_ERR_TOO_LARGE: return "problem too large for the kernel's index arithmetic";
+        default: return "unknown error code";
+    }
+}
+
+int dfa_index_map(int32_t N, int32_t H, dfa_branch_t br, const int32_t* head_offsets, int32_t* out_idx) {
+    if (!out_idx) return DFA_ERR_NULL;
+    if (H <= 0 || N <= 0 || br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    const int32_t per_seg = br.w / br.r, per_head = N / br.r;
+    for (int32_t h = 0; h < H; ++h) {
+        const int32_t o = head_offsets ? head_offsets[h] : h % br.r;
+        if (o < 0 || o >= br.r) return DFA_ERR_SHAPE;
+        int32_t* dst = out_idx + (int64_t)h * per_head;
+        for (int32_t slot = 0; slot < per_head; ++slot)
+            dst[slot] = (slot / per_seg) * br.w + o + (slot % per_seg) * br.r;
+    }
+    return DFA_OK;
+}
+
+int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t* head_offsets,
+                         int32_t* d_out_idx, void* stream) {
+    if (!d_out_idx) return DFA_ERR_NULL;
+    if (H <= 0 || N <= 0 || br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    HeadOffsets offs;
+    const int rc = make_offsets(head_offsets, H, br.r, &offs);
+    if (rc != DFA_OK) return rc;
+    return launch_index_map(N, H, br.w, br.r, offs, d_out_idx, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+int dfa_forward(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                void* out, float* lse, void* stream) {
+    try {
+        return forward_impl(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets,
+                            out, dt == DFA_F32, lse, stream);
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+}
+
+int dfa_forward_branch(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                       dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                       float scale, dfa_branch_t br, const int32_t* head_offsets,
+                       float* out_b, float* lse_b, void* stream) {
+    if (!lse_b) return DFA_ERR_NULL;
+    try {
+        return forward_impl(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, &br, 1, head_offsets,
+                            out_b, true, lse_b, stream);
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+}
+
+int dfa_merge(const float* out_b, const float* lse_b, int32_t nb, int32_t B, int32_t H, int32_t N,
+              int32_t D, dfa_dtype_t dt, void* out, float* lse, void* stream) {
+    if (!out_b || !lse_b || !out) return DFA_ERR_NULL;
+    if (nb < 1 || nb > DFA_MAX_BRANCHES) return DFA_ERR_BRANCHES;
+    const int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    if (reinterpret_cast<uintptr_t>(out_b) % 16 || reinterpret_cast<uintptr_t>(out) % 16) return DFA_ERR_ALIGN;
+    return launch_merge(out_b, lse_b, nb, B, H, N, dt == DFA_BF16, out, lse,
+                        static_cast<hipStream_t>(stream)) == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+int dfa_gather(const void* x, dfa_strides_t sx, int32_t B, int32_t H, int32_t N, int32_t D,
+               dfa_dtype_t dt, dfa_branch_t br, const int32_t* head_offsets, void* xg, void* stream) {
+    if (!x || !xg) return DFA_ERR_NULL;
+    int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    if (br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    HeadOffsets offs;
+    rc = make_offsets(head_offsets, H, br.r, &offs);
+    if (rc != DFA_OK) return rc;
+    if (!aligned_rows(x, sx, elem_size(dt)) || reinterpret_cast<uintptr_t>(xg) % 16) return DFA_ERR_ALIGN;
+    return launch_gather(x, sx.b, sx.n, sx.h, B, H, N, elem_size(dt), br.w, br.r, offs, xg,
+                         static_cast<hipStream_t>(stream)) == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+int dfa_scatter(const void* og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                dfa_branch_t br, const int32_t* head_offsets, void* out, void* stream) {
+    if (!og || !out) return DFA_ERR_NULL;
+    int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    if (br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    HeadOffsets offs;
+    rc = make_offsets(head_offsets, H, br.r, &offs);
+    if (rc != DFA_OK) return rc;
+    if (reinterpret_cast<uintptr_t>(og) % 16 || reinterpret_cast<uintptr_t>(out) % 16) return DFA_ERR_ALIGN;
+    return launch_scatter(og, B, H, N, elem_size(dt), br.w, br.r, offs, out,
+                          static_cast<hipStream_t>(stream)) == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
+                      const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
+                      int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* items) {
+    if (!n_tiles || !n_rows || !n_segs || !n_items) return DFA_ERR_NULL;
+    if (B <= 0) return DFA_ERR_SHAPE;
+    const int rc = check_branches(H, N, branches, nb, head_offsets);
+    if (rc != DFA_OK) return rc;
+    try {
+        HostPlan hp;
+        build_plan(B, H, N, branches, nb, head_offsets, plan_order_mode(), &hp);
+        *n_tiles = (int32_t)hp.tiles.size();
+        *n_rows = (int32_t)hp.rows.size();
+        *n_segs = (int32_t)hp.segs.size();
+        *n_items = (int32_t)hp.items.size();
+        if (tiles)
+            for (size_t t = 0; t < hp.tiles.size(); ++t) {
+                const Tile& x = hp.tiles[t];
+                const int32_t rec[6] = {x.h, x.row_begin, x.nrows, x.seg_begin, x.nseg, 0};
+                std::memcpy(tiles + 6 * t, rec, sizeof(rec));
+            }
+        if (rows) std::memcpy(rows, hp.rows.data(), hp.rows.size() * sizeof(int32_t));
+        if (segs)
+            for (size_t s = 0; s < hp.segs.size(); ++s) {
+                segs[3 * s] = hp.segs[s].key0;
+                segs[3 * s + 1] = hp.segs[s].stride;
+                segs[3 * s + 2] = hp.segs[s].count;
+            }
+        if (items)
+            for (size_t i = 0; i < hp.items.size(); ++i) {
+                items[2 * i] = hp.items[i].tile;
+                items[2 * i + 1] = hp.items[i].b;
+            }
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+    return DFA_OK;
+}
+
+int dfa_release_plans(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int rc = DFA_OK;
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (auto& kv : g_plans) {
+        if (hipSetDevice(kv.second.device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+            hipFree(kv.second.base) != hipSuccess)
+            rc = DFA_ERR_LAUNCH;
+    }
+    g_plans.clear();
+    if (have_cur) (void)hipSetDevice(cur);
+    return rc;
+}
+
+int dfa_forward_timed(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                      dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                      float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                      void* out, float* lse, void* stream, int32_t iters, float* ms) {
+    if (!ms) return DFA_ERR_NULL;
+    if (iters < 1) return DFA_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // one untimed call builds the plan and surfaces argument errors
+    int rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse, stream);
+    if (rc != DFA_OK) return rc;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return DFA_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return DFA_ERR_LAUNCH; }
+    bool ok = hipEventRecord(e0, st) == hipSuccess;
+    for (int i = 0; ok && i < iters && rc == DFA_OK; ++i)
+        rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse, stream);
+    ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+    float total = 0.f;
+    ok = ok && hipEventElapsedTime(&total, e0, e1) == hipSuccess;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != DFA_OK) return rc;
+    if (!ok) return DFA_ERR_LAUNCH;
+    *ms = total / iters;
+    return DFA_OK;
+}
+
+}  // extern "C"

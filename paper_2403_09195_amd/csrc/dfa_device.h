@@ -1,0 +1,66 @@
+// Shared device-side declarations of the dilated-attention kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "dfa_plan.h"
+
+namespace dfa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kD = DFA_HEAD_DIM;        // head dimension
+constexpr int kKeyTile = 64;            // keys staged in LDS per step
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Arguments of the fused forward kernels.  Strides are in elements.
+struct FwdParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    int64_t sqb, sqn, sqh;
+    int64_t skb, skn, skh;
+    int64_t svb, svn, svh;
+    void* out;          // [B, N, H, D] contiguous
+    float* lse;         // [B, H, N] or nullptr
+    const Tile* tiles;
+    const int32_t* rows;
+    const KeySeg* segs;
+    const Item* items;
+    int32_t H, N;
+    float scale;        // multiplies q.k
+};
+
+// Per-head start offsets of the stand-alone indexer / gather / scatter kernels, passed by
+// value: explicit tables are limited to kMaxExplicitHeads heads, h mod r has no limit.
+constexpr int kMaxExplicitHeads = 128;
+struct HeadOffsets {
+    int32_t explicit_table;             // 0: o = h mod r
+    int32_t o[kMaxExplicitHeads];
+};
+
+// Kept-row indexer of Eq. 1: row j of the segment whose first kept row is `first`.
+__device__ __forceinline__ int32_t kept_row(int32_t first, int32_t stride, int32_t j) {
+    return first + stride * j;
+}
+// First kept row of segment i for start offset o.
+__device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o) {
+    return i * w + o;
+}
+
+// Launchers (defined in the .hip files); every one returns the hipError_t of the launch.
+hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
+hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
+hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,
+                            int32_t* d_idx, hipStream_t st);
+hipError_t launch_gather(const void* x, int64_t sb, int64_t sn, int64_t sh, int32_t B, int32_t H,
+                         int32_t N, int esize, int32_t w, int32_t r, const HeadOffsets& offs,
+                         void* xg, hipStream_t st);
+hipError_t launch_scatter(const void* og, int32_t B, int32_t H, int32_t N, int esize, int32_t w,
+                          int32_t r, const HeadOffsets& offs, void* out, hipStream_t st);
+hipError_t launch_merge(const float* out_b, const float* lse_b, int32_t nb, int32_t B, int32_t H,
+                        int32_t N, bool out_bf16, void* out, float* lse, hipStream_t st);
+
+}  // namespace dfa

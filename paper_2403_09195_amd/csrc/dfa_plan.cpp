@@ -1,0 +1,138 @@
+#include "dfa_plan.h"
+
+#include <algorithm>
+#include <map>
+#include <numeric>
+
+namespace dfa {
+
+int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets) {
+    if (nb < 1 || nb > DFA_MAX_BRANCHES) return DFA_ERR_BRANCHES;
+    if (!br) return DFA_ERR_NULL;
+    if (H <= 0 || N <= 0) return DFA_ERR_SHAPE;
+    for (int x = 0; x < nb; ++x) {
+        const int32_t w = br[x].w, r = br[x].r;
+        if (r < 1 || w < r || w > N || N % w != 0 || w % r != 0) return DFA_ERR_SHAPE;
+        if (offsets)
+            for (int h = 0; h < H; ++h) {
+                const int32_t o = offsets[(int64_t)x * H + h];
+                if (o < 0 || o >= r) return DFA_ERR_SHAPE;
+            }
+    }
+    return DFA_OK;
+}
+
+void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+                const int32_t* offsets, int order_mode, HostPlan* plan) {
+    plan->tiles.clear();
+    plan->rows.clear();
+    plan->segs.clear();
+    plan->items.clear();
+
+    std::vector<int64_t> tile_cost;   // (query, key) pairs of each tile
+    for (int32_t h = 0; h < H; ++h) {
+        // signature of a row: for each branch the segment that keeps it, or -1
+        std::map<std::vector<int32_t>, std::vector<int32_t>> groups;
+        std::vector<int32_t> sig(nb);
+        for (int32_t n = 0; n < N; ++n) {
+            for (int x = 0; x < nb; ++x) {
+                const int32_t o = head_offset(offsets, H, x, h, br[x].r);
+                sig[x] = (n % br[x].r == o) ? n / br[x].w : -1;
+            }
+            groups[sig].push_back(n);
+        }
+        for (const auto& g : groups) {
+            const std::vector<int32_t>& s = g.first;
+            const std::vector<int32_t>& rows = g.second;
+            const int32_t seg_begin = (int32_t)plan->segs.size();
+            int32_t nseg = 0;
+            int64_t keys = 0;
+            for (int x = 0; x < nb; ++x) {
+                if (s[x] < 0) continue;
+                const int32_t o = head_offset(offsets, H, x, h, br[x].r);
+                plan->segs.push_back(KeySeg{s[x] * br[x].w + o, br[x].r, br[x].w / br[x].r, 0});
+                keys += br[x].w / br[x].r;
+                ++nseg;
+            }
+            for (size_t lo = 0; lo < rows.size(); lo += kTileRows) {
+                const int32_t cnt = (int32_t)std::min<size_t>(kTileRows, rows.size() - lo);
+                Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, 0};
+                plan->rows.insert(plan->rows.end(), rows.begin() + lo, rows.begin() + lo + cnt);
+                plan->tiles.push_back(t);
+                tile_cost.push_back(keys * cnt);
+            }
+        }
+    }
+
+    // Launch order.  Workgroup i runs on die i mod 8, each die has its own L2, and the tiles
+    // of one (b, h) read the same K/V rows: keep a (b, h) unit on one die when there are
+    // enough units to balance the dies, otherwise spread single tiles.  Within a die the
+    // heaviest tiles go first so the tail of the launch is made of short ones.
+    const int32_t T = (int32_t)plan->tiles.size();
+    std::vector<std::vector<int32_t>> tiles_of_head(H);
+    std::vector<int64_t> head_cost(H, 0);
+    for (int32_t t = 0; t < T; ++t) {
+        tiles_of_head[plan->tiles[t].h].push_back(t);
+        head_cost[plan->tiles[t].h] += tile_cost[t];
+    }
+    std::vector<std::vector<Item>> per_die(kNumXcd);
+    std::vector<int64_t> die_cost(kNumXcd, 0);
+    auto lightest = [&]() {
+        return (int)(std::min_element(die_cost.begin(), die_cost.end()) - die_cost.begin());
+    };
+    const bool by_unit = (int64_t)B * H >= 4 * kNumXcd;
+    if (by_unit) {
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t h = 0; h < H; ++h) {
+                const int d = lightest();
+                for (int32_t t : tiles_of_head[h]) per_die[d].push_back(Item{t, b});
+                die_cost[d] += head_cost[h];
+            }
+    } else {
+        std::vector<int32_t> order(T);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t a, int32_t c) { return tile_cost[a] > tile_cost[c]; });
+        for (int32_t t : order)
+            for (int32_t b = 0; b < B; ++b) {
+                const int d = lightest();
+                per_die[d].push_back(Item{t, b});
+                die_cost[d] += std::max<int64_t>(tile_cost[t], 1);
+            }
+    }
+    // Order inside a die.  Mode 2 (default): the multi-branch tiles of one (b, h) stay together,
+    // heaviest first, so that the workgroups running at the same time read the same K/V rows
+    // from the die's L2; the cheap single-branch tiles of all units follow as filler for the
+    // end of the launch.  Mode 1: strictly unit after unit.  Mode 0: heaviest first overall.
+    size_t longest = 0;
+    for (auto& v : per_die) {
+        if (order_mode == 0 || !by_unit) {
+            std::stable_sort(v.begin(), v.end(), [&](const Item& a, const Item& c) {
+                return tile_cost[a.tile] > tile_cost[c.tile];
+            });
+        } else {
+            // v is unit-major already; sort each unit's run by cost, then (mode 2) move the
+            // single-segment tiles behind everything else, keeping their order
+            size_t lo = 0;
+            while (lo < v.size()) {
+                size_t hi = lo;
+                while (hi < v.size() && v[hi].b == v[lo].b &&
+                       plan->tiles[v[hi].tile].h == plan->tiles[v[lo].tile].h) ++hi;
+                std::stable_sort(v.begin() + lo, v.begin() + hi, [&](const Item& a, const Item& c) {
+                    return tile_cost[a.tile] > tile_cost[c.tile];
+                });
+                lo = hi;
+            }
+            if (order_mode == 2)
+                std::stable_partition(v.begin(), v.end(),
+                                      [&](const Item& a) { return plan->tiles[a.tile].nseg > 1; });
+        }
+        longest = std::max(longest, v.size());
+    }
+    plan->items.reserve(longest * kNumXcd);
+    for (size_t p = 0; p < longest; ++p)
+        for (int d = 0; d < kNumXcd; ++d)
+            plan->items.push_back(p < per_die[d].size() ? per_die[d][p] : Item{-1, 0});
+}
+
+}  // namespace dfa

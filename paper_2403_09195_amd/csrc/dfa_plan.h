@@ -1,0 +1,54 @@
+// Launch plan of the fused dilated-attention kernels: host-side construction.
+//
+// Query rows of one head are grouped by the set of (branch, segment) pairs that keep them
+// (section 3.1, Eq. 1: a row is kept by branch (w, r) iff n mod r equals the head's start
+// offset, and its keys are the kept rows of segment floor(n / w)).  Rows of one group share
+// one key list per member branch, so a tile of such rows runs a single online softmax over
+// the concatenated key lists - which is exactly the log-sum-exp merge of the branches.
+#pragma once
+#include <cstdint>
+#include <vector>
+#include "../../include/dfa.h"
+
+namespace dfa {
+
+constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
+constexpr int kNumXcd = 8;       // MI355X: 8 accelerator dies, workgroups dealt round-robin
+
+struct KeySeg {      // kept keys of one segment of one branch: key0 + stride * j, j < count
+    int32_t key0, stride, count, pad;
+};
+struct Tile {
+    int32_t h;          // head
+    int32_t row_begin;  // first entry in the row list
+    int32_t nrows;      // 1 .. kTileRows
+    int32_t seg_begin;  // first entry in the key-segment list
+    int32_t nseg;       // 0 = rows kept by no branch (output 0, lse -inf)
+    int32_t pad;
+};
+struct Item {        // one workgroup of the launch
+    int32_t tile;    // -1 = padding, nothing to do
+    int32_t b;       // batch index
+};
+
+struct HostPlan {
+    std::vector<Tile> tiles;
+    std::vector<int32_t> rows;
+    std::vector<KeySeg> segs;
+    std::vector<Item> items;
+};
+
+// Validates the branch list (DFA_OK or a negative status).  offsets: [nb][H] or nullptr.
+int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets);
+
+// Start offset of head h in branch x.
+inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t h, int32_t r) {
+    return offsets ? offsets[(int64_t)x * H + h] : h % r;
+}
+
+// Builds tiles, row lists, key segments and the launch order for B images.
+// order_mode: 2 = default (see dfa_plan.cpp), 0 and 1 are alternatives kept for measurement.
+void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+                const int32_t* offsets, int order_mode, HostPlan* plan);
+
+}  // namespace dfa

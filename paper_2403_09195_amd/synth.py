@@ -14,6 +14,8 @@ iid N(0,1) tensors with the paper's shapes (1024x1024 image, patch 16 ->
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 _M64 = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -40,22 +42,33 @@ def _stream_key(seed: int, tensor_id: int) -> np.uint64:
     return b[0]
 
 
+def _normal_chunk(key, first, count, out):
+    idx = np.arange(first, first + count, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        c = key + idx * np.uint64(2)
+    b1 = _mix(c)
+    b2 = _mix(c + np.uint64(1))
+    # 53-bit uniforms; u1 in (0,1] so the logarithm is finite
+    u1 = ((b1 >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+    u2 = (b2 >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+    out[:] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+
+
 def normal_f64(seed: int, tensor_id: int, count: int, start: int = 0) -> np.ndarray:
-    """`count` iid N(0,1) draws in fp64: elements start .. start+count-1 of the stream."""
+    """`count` iid N(0,1) draws in fp64: elements start .. start+count-1 of the stream.
+
+    Chunks are filled by a few threads; the values do not depend on the chunking."""
     key = _stream_key(seed, tensor_id)
     out = np.empty(count, dtype=np.float64)
-    chunk = 1 << 22
-    for lo in range(0, count, chunk):
-        hi = min(count, lo + chunk)
-        idx = np.arange(start + lo, start + hi, dtype=np.uint64)
-        with np.errstate(over="ignore"):
-            c = key + idx * np.uint64(2)
-        b1 = _mix(c)
-        b2 = _mix(c + np.uint64(1))
-        # 53-bit uniforms; u1 in (0,1] so the logarithm is finite
-        u1 = ((b1 >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
-        u2 = (b2 >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
-        out[lo:hi] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    chunk = 1 << 20
+    spans = [(lo, min(count, lo + chunk)) for lo in range(0, count, chunk)]
+    if len(spans) <= 1:
+        for lo, hi in spans:
+            _normal_chunk(key, start + lo, hi - lo, out[lo:hi])
+        return out
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda s: _normal_chunk(key, start + s[0], s[1] - s[0], out[s[0]:s[1]]), spans))
     return out
 
 

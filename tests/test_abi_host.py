@@ -1,0 +1,150 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, rejects bad
+arguments before touching the GPU, and builds launch plans that cover the operator's definition
+(section 3.1: each kept query row attends the kept rows of its own segment, per branch).
+No GPU needed: nothing here launches a kernel."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2403_09195_amd import binding, build
+    if not os.path.exists(build.LIB_PATH):
+        build.build()
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "dfa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dfa_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    raw = ctypes.CDLL(os.path.join(ROOT, "paper_2403_09195_amd", "libdfa.so"))
+    for name in declared:
+        assert hasattr(raw, name), name
+    assert B.version() >= 100
+    for code in range(0, -8, -1):
+        assert B.error_string(code) != "unknown error code"
+    assert B.error_string(-99) == "unknown error code"
+
+
+def test_host_index_map_matches_eq1_by_hand(B):
+    # N = 16, w = 8, r = 2 (worked by hand from Eq. 1; head start h mod r)
+    assert B.index_map(16, 3, 8, 2) == [[0, 2, 4, 6, 8, 10, 12, 14], [1, 3, 5, 7, 9, 11, 13, 15],
+                                        [0, 2, 4, 6, 8, 10, 12, 14]]
+    assert B.index_map(12, 2, 6, 3, head_offsets=[2, 1]) == [[2, 5, 8, 11], [1, 4, 7, 10]]
+    assert B.index_map(8, 1, 8, 1) == [list(range(8))]
+
+
+def _fwd_rc(mod, **kw):
+    """dfa_forward return code with fake (never dereferenced) pointers."""
+    a = dict(q=0x10000, k=0x20000, v=0x30000, out=0x40000, lse=0x50000, Bsz=1, H=2, N=64, D=64, dt=0,
+             scale=0.125, branches=[(16, 2)], offs=None, sq=None)
+    a.update(kw)
+    st = a["sq"] or mod.Strides(a["N"] * a["H"] * 64, a["H"] * 64, 64)
+    br, nb = mod._branches(a["branches"])
+    if "nb" in kw:
+        nb = kw["nb"]
+    vp = ctypes.c_void_p
+    return mod.lib().dfa_forward(vp(a["q"]), vp(a["k"]), vp(a["v"]), st, st, st, a["Bsz"], a["H"], a["N"], a["D"],
+                               a["dt"], ctypes.c_float(a["scale"]), br, nb, mod._i32_array(a["offs"]),
+                               vp(a["out"]), vp(a["lse"]), None)
+
+
+def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
+    assert _fwd_rc(B, q=None) == -1
+    assert _fwd_rc(B, out=None) == -1
+    assert _fwd_rc(B, D=128) == -2
+    assert _fwd_rc(B, Bsz=0) == -2
+    assert _fwd_rc(B, branches=[(48, 2)]) == -2          # N % w != 0
+    assert _fwd_rc(B, branches=[(16, 3)]) == -2          # w % r != 0
+    assert _fwd_rc(B, branches=[(128, 1)]) == -2         # w > N
+    assert _fwd_rc(B, branches=[(16, 0)]) == -2          # r < 1
+    assert _fwd_rc(B, offs=[[0, 2]]) == -2               # offset outside [0, r)
+    assert _fwd_rc(B, scale=0.0) == -2
+    assert _fwd_rc(B, scale=float("nan")) == -2
+    assert _fwd_rc(B, nb=0) == -3
+    assert _fwd_rc(B, branches=[(16, 1)] * 9) == -3
+    assert _fwd_rc(B, dt=7) == -4
+    assert _fwd_rc(B, q=0x10004) == -5
+    assert _fwd_rc(B, sq=B.Strides(64 * 2 * 64, 2 * 64 + 4, 64)) == -5
+
+
+def _expected_key_sets(N, h, branches, offs):
+    """row -> sorted list of (first key, stride, count), from the definition."""
+    exp = {}
+    for n in range(N):
+        segs = []
+        for x, (w, r) in enumerate(branches):
+            o = (h % r) if offs is None else offs[x][h]
+            if n % r == o:
+                segs.append(((n // w) * w + o, r, w // r))
+        exp[n] = segs
+    return exp
+
+
+@pytest.mark.parametrize("Bsz,H,N,branches,offs", [
+    (1, 1, 256, [(64, 2)], None),
+    (1, 12, 4096, [(1024, 1), (2048, 2), (4096, 4)], None),
+    (16, 12, 4096, [(1024, 1), (2048, 2), (4096, 4)], None),
+    (2, 3, 16384, [(2048, 1), (4096, 2), (8192, 4), (16384, 8)], None),
+    (3, 4, 360, [(120, 3), (180, 2), (360, 5)], [[2, 0, 1, 2], [1, 1, 0, 0], [4, 3, 0, 1]]),
+    (40, 2, 96, [(32, 4), (96, 1)], None),
+])
+def test_plan_covers_the_definition(B, Bsz, H, N, branches, offs):
+    p = B.plan_describe(Bsz, H, N, branches, offs)
+    tiles, rows, segs, items = p["tiles"], p["rows"], p["segs"], p["items"]
+    seen = np.zeros((H, N), dtype=np.int32)
+    for (h, rb, nr, sb, ns, _) in tiles:
+        assert 1 <= nr <= 256
+        exp = _expected_key_sets(N, h, branches, offs) if N <= 4096 else None
+        tile_rows = rows[rb:rb + nr]
+        seen[h, tile_rows] += 1
+        got = [tuple(int(x) for x in segs[s]) for s in range(sb, sb + ns)]
+        if exp is not None:
+            for n in tile_rows:
+                assert got == exp[int(n)], (h, n)
+        else:
+            for n in tile_rows[[0, -1]]:
+                assert got == _expected_key_sets_row(int(n), h, branches, offs)
+    assert np.all(seen == 1)                                    # every (h, n) in exactly one tile
+    assert len(items) % 8 == 0
+    real = items[items[:, 0] >= 0]
+    pairs = set(map(tuple, real.tolist()))
+    assert len(pairs) == len(real) == len(tiles) * Bsz          # every (tile, b) launched once
+    assert real[:, 1].min() == 0 and real[:, 1].max() == Bsz - 1
+    total_pairs = 0
+    for (h, rb, nr, sb, ns, _) in tiles:
+        total_pairs += nr * int(segs[sb:sb + ns, 2].sum()) if ns else 0
+    assert total_pairs == H * sum(N * w // (r * r) for (w, r) in branches)   # N*w/r^2 pairs per branch
+
+
+def _expected_key_sets_row(n, h, branches, offs):
+    out = []
+    for x, (w, r) in enumerate(branches):
+        o = (h % r) if offs is None else offs[x][h]
+        if n % r == o:
+            out.append(((n // w) * w + o, r, w // r))
+    return out
+
+
+def test_plan_keeps_a_unit_on_one_die_when_there_are_enough_units(B):
+    # workgroup i runs on die i mod 8; all tiles of one (b, h) should share a die (and its L2)
+    p = B.plan_describe(16, 12, 4096, [(1024, 1), (2048, 2), (4096, 4)])
+    die_of = {}
+    for i, (t, b) in enumerate(p["items"]):
+        if t < 0:
+            continue
+        unit = (int(b), int(p["tiles"][t][0]))
+        die_of.setdefault(unit, set()).add(i % 8)
+    assert len(die_of) == 16 * 12
+    assert all(len(d) == 1 for d in die_of.values())
+    per_die = np.bincount([next(iter(d)) for d in die_of.values()], minlength=8)
+    assert per_die.min() == per_die.max() == 24
