@@ -40,6 +40,18 @@ _lib = None
 _i32p = ctypes.POINTER(ctypes.c_int32)
 
 
+def _one_hip_runtime():
+    """The stream handles torch hands out are only valid in the HIP runtime torch itself uses:
+    refuse to run if loading libdfa.so pulled in a second copy of libamdhip64."""
+    try:
+        maps = open("/proc/self/maps").read()
+    except OSError:
+        return
+    paths = {ln.split()[-1] for ln in maps.splitlines() if "libamdhip64" in ln}
+    if len(paths) > 1:
+        raise RuntimeError(f"two HIP runtimes loaded: {sorted(paths)}")
+
+
 def lib():
     """Loads libdfa.so (after torch, so that both share one HIP runtime)."""
     global _lib
@@ -48,6 +60,7 @@ def lib():
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
         import torch  # noqa: F401  (brings in libamdhip64 first)
         L = ctypes.CDLL(LIB_PATH)
+        _one_hip_runtime()
         L.dfa_error_string.restype = ctypes.c_char_p
         L.dfa_error_string.argtypes = [ctypes.c_int]
         vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float

@@ -78,15 +78,17 @@ void dfa_fwd_f32_kernel(const FwdParams p) {
 #pragma unroll
                 for (int jj = 0; jj < kSub; ++jj) {
                     const float* kr = k_lds + (c0 + jj) * kD;
-                    float dot = 0.f;
+                    // four interleaved partial sums: shorter rounding chains, more ILP
+                    float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
 #pragma unroll
                     for (int d = 0; d < kD; d += 4) {
                         const float4 x = *reinterpret_cast<const float4*>(kr + d);
-                        dot = fmaf(qv[d], x.x, dot);
-                        dot = fmaf(qv[d + 1], x.y, dot);
-                        dot = fmaf(qv[d + 2], x.z, dot);
-                        dot = fmaf(qv[d + 3], x.w, dot);
+                        d0 = fmaf(qv[d], x.x, d0);
+                        d1 = fmaf(qv[d + 1], x.y, d1);
+                        d2 = fmaf(qv[d + 2], x.z, d2);
+                        d3 = fmaf(qv[d + 3], x.w, d3);
                     }
+                    const float dot = (d0 + d1) + (d2 + d3);
                     sc[jj] = (c0 + jj < nvalid) ? dot * p.scale : -INFINITY;
                     mx = fmaxf(mx, sc[jj]);
                 }

@@ -29,11 +29,11 @@ def _check_bf16(out, lse, o_ref, l_ref, tag=""):
     return mx, mean
 
 
-def _check_f32(out, lse, o_ref, l_ref, tag=""):
+def _check_f32(out, lse, o_ref, l_ref, tag="", tol=F32_MAX):
     mx, mean = error_stats(to_f64(out), o_ref)
-    le = check_lse(to_f64(lse), l_ref, atol=1e-5, rtol=1e-5)
+    le = check_lse(to_f64(lse), l_ref, atol=tol, rtol=1e-5)
     print(f"[{tag}] f32 out max-abs {mx:.3e} mean-abs {mean:.3e} lse max-abs {le:.3e}", flush=True)
-    assert mx <= F32_MAX
+    assert mx <= tol
     return mx
 
 
@@ -107,7 +107,11 @@ def test_fp32_multi_branch_ragged(B, oracle, scale):
     (q, k, v), ex = make_qkv(101, Bsz, N, H, D, "f32")
     out, lse = B.forward(q, k, v, branches, scale, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, scale, head_offsets=offs)
-    _check_f32(out, lse, o_ref, l_ref, f"f32 ragged s={scale}")
+    # scale = 1 is the literal Eq. 2: logits are 8x larger (sigma 8, row maxima 30-40), and so
+    # is the absolute fp32 rounding error of each logit, which the exponential turns into a
+    # relative error of the weights: the 1e-5 bar of the 1/sqrt(D) convention scales to 8e-5;
+    # 3e-5 is asserted.
+    _check_f32(out, lse, o_ref, l_ref, f"f32 ragged s={scale}", tol=1e-5 if scale < 1.0 else 3e-5)
 
 
 # ---------------------------------------------------------------- bf16 path
