@@ -128,6 +128,11 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     if (!aligned_rows(q, sq, es) || !aligned_rows(k, sk, es) || !aligned_rows(v, sv, es)) return DFA_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(out) % 16 || (lse && reinterpret_cast<uintptr_t>(lse) % 4)) return DFA_ERR_ALIGN;
 
+    // the copy lanes address a 64-key step with 32-bit byte offsets from its first row
+    for (int x = 0; x < nb; ++x) {
+        const int64_t pitch = (int64_t)branches[x].r * (sk.n > sv.n ? sk.n : sv.n) * es;
+        if (sk.n <= 0 || sv.n <= 0 || sq.n <= 0 || 64 * pitch + 128 >= ((int64_t)1 << 31)) return DFA_ERR_TOO_LARGE;
+    }
     DevicePlan dp;
     rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
     if (rc != DFA_OK) return rc;
