@@ -142,7 +142,7 @@ constexpr float kRebaseThreshold = 256.0f;
 // straight into the B operands of the second product.  psum = this lane's share of the row
 // sums, taken over the rounded values with a packed dot product.
 __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const float (&m_ref)[2],
-                                          bf16x8 (&pb)[2][2], float (&psum)[2]) {
+                                          u32x4 (&pb)[2][2], float (&psum)[2]) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -153,8 +153,7 @@ __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const
             const float e1 = __builtin_amdgcn_exp2f(fmaf(s[qb][v + 1], c, -m_ref[qb]));
             const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
             acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-            pb[qb][v >> 3][v & 7] = pr[0];
-            pb[qb][v >> 3][(v & 7) + 1] = pr[1];
+            pb[qb][v >> 3][(v & 7) >> 1] = __builtin_bit_cast(uint32_t, pr);   // slots v%8, v%8+1
         }
         psum[qb] = acc;
     }
@@ -191,7 +190,7 @@ __device__ __forceinline__ void tile_step(const uint16_t* kl, const uint16_t* vl
                                           float (&l_run)[2], floatx16 (&oacc)[2][2]) {
     const int j = lane & 31, g = lane >> 5;
     floatx16 sacc[2][2];                   // [key block][query block]
-    bf16x8 pb[2][2][2];                    // [key block][query block][16-key step]
+    u32x4 pb[2][2][2];                     // [key block][query block][16-key step], bf16 pairs
 
     auto scores = [&](int ks) {
         const int rho = 32 * ks + j;
@@ -215,6 +214,7 @@ __device__ __forceinline__ void tile_step(const uint16_t* kl, const uint16_t* vl
     };
     auto mask_tail = [&](int ks) {
         // end of a key list: register v of lane (j, g) is tile position 32*ks + 16*(v/8) + 8*g + v%8
+        asm volatile("" ::: "memory");     // keeps this a branch: full steps must not pay for the selects
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int pos = 32 * ks + 16 * (v >> 3) + 8 * g + (v & 7);
@@ -254,7 +254,7 @@ __device__ __forceinline__ void tile_step(const uint16_t* kl, const uint16_t* vl
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb)
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[ks][qb][st], oacc[db][qb], 0, 0, 0);
+                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pb[ks][qb][st]), oacc[db][qb], 0, 0, 0);
             }
     };
 
