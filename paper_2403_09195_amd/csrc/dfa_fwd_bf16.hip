@@ -144,18 +144,32 @@ constexpr float kRebaseThreshold = 256.0f;
 __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const float (&m_ref)[2],
                                           u32x4 (&pb)[2][2], float (&psum)[2]) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    // Written stage by stage (all exponents, then all exponentials, then all conversions) and
+    // with four independent partial sums: a vector instruction that needs the result of the one
+    // just before it stalls the wave, so dependent instructions are kept far apart.
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        float acc = 0.f;
+        float t[16];
 #pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-            const float e0 = __builtin_amdgcn_exp2f(fmaf(s[qb][v], c, -m_ref[qb]));
-            const float e1 = __builtin_amdgcn_exp2f(fmaf(s[qb][v + 1], c, -m_ref[qb]));
-            const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
-            acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-            pb[qb][v >> 3][(v & 7) >> 1] = __builtin_bit_cast(uint32_t, pr);   // slots v%8, v%8+1
+        for (int v = 0; v < 16; ++v) t[v] = fmaf(s[qb][v], c, -m_ref[qb]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t[v] = __builtin_amdgcn_exp2f(t[v]);
+        bf16x2 pr[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            pr[v] = bf16x2{(__bf16)t[2 * v], (__bf16)t[2 * v + 1]};
+            pb[qb][v >> 2][v & 3] = __builtin_bit_cast(uint32_t, pr[v]);   // slots 2v%8, 2v%8+1 of step v/4
         }
-        psum[qb] = acc;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        a0 = __builtin_amdgcn_fdot2_f32_bf16(pr[0], ones, a0, false);
+        a1 = __builtin_amdgcn_fdot2_f32_bf16(pr[1], ones, a1, false);
+        a2 = __builtin_amdgcn_fdot2_f32_bf16(pr[2], ones, a2, false);
+        a3 = __builtin_amdgcn_fdot2_f32_bf16(pr[3], ones, a3, false);
+        a0 = __builtin_amdgcn_fdot2_f32_bf16(pr[4], ones, a0, false);
+        a1 = __builtin_amdgcn_fdot2_f32_bf16(pr[5], ones, a1, false);
+        a2 = __builtin_amdgcn_fdot2_f32_bf16(pr[6], ones, a2, false);
+        a3 = __builtin_amdgcn_fdot2_f32_bf16(pr[7], ones, a3, false);
+        psum[qb] = (a0 + a1) + (a2 + a3);
     }
 }
 
