@@ -19,6 +19,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
 WORKLOAD = "throughput"
+# HBM bytes per launch of the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
+# the copy-kernel calibration (profiles/dfa_fwd_bf16_throughput.md); None for other workloads
+MEASURED_HBM_TRAFFIC_BYTES = {"throughput": 744679424}
 
 
 def main():
@@ -28,6 +31,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=WORKLOAD, help="name in synth.CONFIGS (default: throughput)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs: "
@@ -42,6 +47,18 @@ def main():
         sys.exit("bench.py: no GPU visible")
     binding.lib()
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        # a plain copy kernel of known size: rocprofv3's FETCH_SIZE / WRITE_SIZE for it give the
+        # factor between the counters and real HBM bytes
+        n = 1 << 28                                   # 256 MiB read + 256 MiB written per copy
+        a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_each_way": n, "copies": 5}))
+        return
 
     cfg = synth.CONFIGS[args.workload]
     Bsz, H, N, D, branches = cfg["B"], cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
@@ -84,14 +101,14 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        bs = min(Bsz, 8)
+        bs = Bsz                                      # the oracle needs only seconds for the whole batch
         sub = tuple(np.ascontiguousarray(a[:bs]) for a in exact)
         t0 = time.perf_counter()
         dfa_oracle.forward(*sub, branches, scale)
         dt = time.perf_counter() - t0
         cpu = {"value": synth.useful_flops(bs, H, N, D, branches) / dt / 1e12, "unit": "TFLOP/s",
                "cores": dfa_oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
-               "sample": f"first {bs} of {Bsz} images, all {H} heads ({bs * H} of {Bsz * H} independent (b,h) units), fp64"}
+               "sample": f"the whole workload: {bs} of {Bsz} images, all {H} heads ({bs * H} independent (b,h) units), fp64"}
 
     line = {
         "metric": "dilated-attention TFLOP/s (useful attention FLOPs, 4*D per kept query-key pair)",
@@ -105,7 +122,9 @@ def main():
         "useful_flops_per_step": flops,
         "sampled_max_abs_err_vs_oracle": max_err,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.workload),
+                     "algorithmic_bytes": Bsz * N * H * (4 * D * (2 if cfg["dtype"] == "bf16" else 4) + 4),
                      "kernel": "dfa_fwd_bf16_kernel", "kernel_ms": kern_ms},
         "cpu_baseline": cpu,
     }
