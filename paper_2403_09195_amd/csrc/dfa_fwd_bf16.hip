@@ -2,19 +2,19 @@
 //
 // One workgroup (4 waves) owns a tile of up to 256 query rows that share the same key lists
 // (section 3.1: all of them are kept by the same branches and fall into the same segment of
-// each).  It walks the key lists of its member branches one after the other, 64 keys at a
-// time, carrying ONE online-softmax state (reference exponent, running sum, accumulator) per
-// query row across all of them: continuing the softmax over the next branch's keys is the
-// log-sum-exp merge of the branches, so no partial result ever leaves the registers.
+// each).  It walks the key lists of its member branches one after the other, carrying ONE
+// online-softmax state (reference exponent, running sum, accumulator) per query row across all
+// of them: continuing the softmax over the next branch's keys is the log-sum-exp merge of the
+// branches, so no partial result ever leaves the registers.
 //
 // Gather (Eq. 1) happens in the global->LDS copies (key j of a segment is row first + r*j),
 // placement (Eq. 3) in the final store (each query row is written back at its own token).
 //
 // Data movement: K and V rows go from global memory straight into LDS (global_load_lds, 16
-// bytes per lane, no staging registers), three 64-key stages deep, so a copy has two full
-// compute steps to land.  Each wave-level copy fills 1 KB = 8 rows of 128 bytes; which
-// global row and 16-byte chunk a lane fetches is free, which is how the row permutation and
-// the bank swizzle below are applied.
+// bytes per lane, no staging registers) in stages of 64 keys, four stages in LDS, two of them
+// in flight while a third is being consumed.  Each wave-level copy fills 1 KB = 8 rows of 128
+// bytes; which global row and 16-byte chunk a lane fetches is free, which is how the row
+// permutation and the bank swizzle below are applied.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16, wave64; lane = 32*g + j):
 //   S^T = K~ Q~^T : A = K rows (32 keys x 16 d), B = Q^T (16 d x 32 queries).  The result puts
@@ -30,13 +30,19 @@
 //                   16-lane group, delivered key-contiguous per lane).
 // Each wave handles 64 query rows (two 32-row blocks), so every K / V^T fragment read from
 // LDS feeds two MFMAs.
+//
+// Schedule: the key walk is software-pipelined in beats of 32 keys.  In one beat a wave issues
+// the MFMAs of the NEXT block's scores and of the PREVIOUS block's accumulation while its
+// vector ALU turns the CURRENT block's scores into probabilities, all in one hand-ordered
+// instruction stream (see beat()), so matrix cores and vector ALU overlap inside each wave
+// and not only between the two waves that share a SIMD.
 #include "dfa_device.h"
 
 namespace dfa {
 
 namespace {
 
-constexpr int kStages = 3;                 // 64-key K/V stages in flight
+constexpr int kStages = 4;                 // 64-key K/V stages in LDS
 constexpr int kRowElems = kD;              // LDS rows are the 128-byte rows of memory, unpadded
 constexpr int kStageElems = kKeyTile * kRowElems;
 
@@ -48,9 +54,26 @@ typedef short short8v __attribute__((ext_vector_type(8)));
 #define DFA_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define DFA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-__device__ __forceinline__ float wave_half_xchg(float x) {
-    // value held by the lane that owns the other 16 keys of the same query (lane ^ 32)
-    return __shfl_xor(x, 32, 64);
+// The two lanes that share a query (lane and lane ^ 32, each with 16 of a block's 32 keys)
+// combine their values.  v_permlane32_swap exchanges the upper half of its first operand with
+// the lower half of its second; fed x twice it leaves x of the lower half in both halves of
+// the first and x of the upper half in both halves of the second.  Written as inline assembly
+// (with the idle states a vector write before it and a vector read after it need): the
+// compiler's builtin hands back the first result for both.
+__device__ __forceinline__ void wave_half_pair(float x, float& lo, float& hi) {
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float wave_half_max(float x) {
+    float lo, hi;
+    wave_half_pair(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float wave_half_sum(float x) {
+    float lo, hi;
+    wave_half_pair(x, lo, hi);
+    return lo + hi;
 }
 
 // 16-byte chunk swizzle of the K stage: chunk c of LDS row rho sits at chunk c ^ k_swizzle(rho).
@@ -106,11 +129,13 @@ __device__ __forceinline__ const void* uniform_ptr(const void* p) {
 }
 
 // Per-lane constants of the global->LDS copies.  A wave issues 2 K copies and 2 V copies per
-// step; copy u of wave w fills LDS rows 8*(2w+u) .. +7, lane L lands at row L/8, chunk L%8.
+// step; copy u of wave w fills LDS rows rho = 8*(2w+u) .. +7, lane L lands at row L/8, chunk
+// L%8.  Stored for u = 0; for u = 1 (rho + 8) the key position sigma(rho) grows by 4, the
+// swizzled chunk flips its top bit and the V position grows by 8.
 struct CopyLane {
-    int kpos[2];       // tile position of the key whose row this lane fetches (K copies)
-    int kchunk[2];     // byte offset of the 16-byte chunk of that row
-    int vpos[2];       // same for V (position order, chunks in place)
+    int kpos;          // tile position of the key whose row this lane fetches (K copy 0)
+    int kchunk;        // byte offset of the 16-byte chunk of that row
+    int vpos;          // same for V (position order, chunks in place)
     int vchunk;
 };
 
@@ -128,8 +153,8 @@ __device__ __forceinline__ void issue_stage(const FwdParams& p, const uint16_t* 
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const uint32_t blk = (uint32_t)(2 * wave + u) * 1024u;
-        copy16_to_lds(kb, (uint32_t)min(cl.kpos[u], room) * kpitch + cl.kchunk[u], k_stage + blk);
-        copy16_to_lds(vb, (uint32_t)min(cl.vpos[u], room) * vpitch + cl.vchunk, v_stage + blk);
+        copy16_to_lds(kb, (uint32_t)min(cl.kpos + 4 * u, room) * kpitch + (cl.kchunk ^ (64 * u)), k_stage + blk);
+        copy16_to_lds(vb, (uint32_t)min(cl.vpos + 8 * u, room) * vpitch + cl.vchunk, v_stage + blk);
     }
 }
 
@@ -139,37 +164,24 @@ constexpr float kRebaseThreshold = 256.0f;
 
 // Softmax numerators of one 32-key block against the current reference exponents m_ref (no
 // row maximum is taken here): p = exp2(c*s - m_ref), rounded to bf16 (nearest even) and packed
-// straight into the B operands of the second product.  psum = this lane's share of the row
-// sums, taken over the rounded values with a packed dot product.
+// straight into the B operands of the second product; psum = this lane's share of the row
+// sums, in fp32 over the unrounded values.  Plain form, used after a rebase; beat() does the
+// same arithmetic in its hand-ordered stream.
 __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const float (&m_ref)[2],
                                           u32x4 (&pb)[2][2], float (&psum)[2]) {
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    // Written stage by stage (all exponents, then all exponentials, then all conversions) and
-    // with four independent partial sums: a vector instruction that needs the result of the one
-    // just before it stalls the wave, so dependent instructions are kept far apart.
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        float t[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) t[v] = fmaf(s[qb][v], c, -m_ref[qb]);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) t[v] = __builtin_amdgcn_exp2f(t[v]);
-        bf16x2 pr[8];
+        float a0 = 0.f, a1 = 0.f;
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            pr[v] = bf16x2{(__bf16)t[2 * v], (__bf16)t[2 * v + 1]};
-            pb[qb][v >> 2][v & 3] = __builtin_bit_cast(uint32_t, pr[v]);   // slots 2v%8, 2v%8+1 of step v/4
+            const float e0 = __builtin_amdgcn_exp2f(fmaf(s[qb][2 * v], c, -m_ref[qb]));
+            const float e1 = __builtin_amdgcn_exp2f(fmaf(s[qb][2 * v + 1], c, -m_ref[qb]));
+            const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
+            pb[qb][v >> 2][v & 3] = __builtin_bit_cast(uint32_t, pr);   // slots 2v%8, 2v%8+1 of step v/4
+            a0 += e0;
+            a1 += e1;
         }
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        a0 = __builtin_amdgcn_fdot2_f32_bf16(pr[0], ones, a0, false);
-        a1 = __builtin_amdgcn_fdot2_f32_bf16(pr[1], ones, a1, false);
-        a2 = __builtin_amdgcn_fdot2_f32_bf16(pr[2], ones, a2, false);
-        a3 = __builtin_amdgcn_fdot2_f32_bf16(pr[3], ones, a3, false);
-        a0 = __builtin_amdgcn_fdot2_f32_bf16(pr[4], ones, a0, false);
-        a1 = __builtin_amdgcn_fdot2_f32_bf16(pr[5], ones, a1, false);
-        a2 = __builtin_amdgcn_fdot2_f32_bf16(pr[6], ones, a2, false);
-        a3 = __builtin_amdgcn_fdot2_f32_bf16(pr[7], ones, a3, false);
-        psum[qb] = (a0 + a1) + (a2 + a3);
+        psum[qb] = a0 + a1;
     }
 }
 
@@ -182,7 +194,7 @@ __device__ __forceinline__ void rebase_block(const floatx16 (&s)[2], float c, fl
         float mx = s[qb][0];
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[qb][v]);
-        mx = fmaxf(mx, wave_half_xchg(mx));
+        mx = wave_half_max(mx);
         const float m_new = fmaxf(m_ref[qb], mx * c);
         const float alpha = __builtin_amdgcn_exp2f(m_ref[qb] - m_new);   // exp2(-inf) = 0 at the start
         m_ref[qb] = m_new;
@@ -194,95 +206,139 @@ __device__ __forceinline__ void rebase_block(const floatx16 (&s)[2], float c, fl
     }
 }
 
-// One 64-key step: S^T, softmax numerators, O^T accumulation, in two 32-key blocks.  The
-// scheduling fences keep the phases apart so that at most two score blocks, two packed
-// probability blocks and one set of LDS fragments are alive at a time (256 registers per lane
-// are all there is at two waves per SIMD); inside a phase the matrix cores work on one block
-// while the vector ALU exponentiates the other.
-__device__ __forceinline__ void tile_step(const uint16_t* kl, const uint16_t* vl, const bf16x8 (&qf)[2][4],
-                                          int lane, int nvalid, float c, float (&m_ref)[2],
-                                          float (&l_run)[2], floatx16 (&oacc)[2][2]) {
-    const int j = lane & 31, g = lane >> 5;
-    floatx16 sacc[2][2];                   // [key block][query block]
-    u32x4 pb[2][2][2];                     // [key block][query block][16-key step], bf16 pairs
+// Lane constants of the LDS fragment reads.
+struct FragLane {
+    int k;        // element offset inside a 32-key K block of the 16-byte chunk for d-step 0; the chunk
+                  // of d-step kk is (2*kk + g) ^ swizzle, i.e. this offset with 16*kk xor-ed in
+    int v;        // element offset inside a 32-key V block of this lane's transposed-read address
+};
 
-    auto scores = [&](int ks) {
-        const int rho = 32 * ks + j;
-        const uint16_t* krow = kl + rho * kRowElems;
-        const int swz = k_swizzle(rho);
+// End of a key list: every score of a 32-key block at or past position nvalid becomes -inf.
+// Register v of lane (j, g) is block position 16*(v/8) + 8*g + v%8.
+__device__ __forceinline__ void mask_block(floatx16 (&s)[2], int g, int nvalid) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + 8 * ((2 * kk + g) ^ swz));
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                if (kk == 0) {
-                    floatx16 z;
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) z[v] = 0.f;
-                    sacc[ks][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], z, 0, 0, 0);
-                } else {
-                    sacc[ks][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], sacc[ks][qb], 0, 0, 0);
-                }
-            }
+    for (int v = 0; v < 16; ++v) {
+        const int pos = 16 * (v >> 3) + 8 * g + (v & 7);
+        if (pos >= nvalid) {
+            s[0][v] = -INFINITY;
+            s[1][v] = -INFINITY;
         }
-    };
-    auto mask_tail = [&](int ks) {
-        // end of a key list: register v of lane (j, g) is tile position 32*ks + 16*(v/8) + 8*g + v%8
-        asm volatile("" ::: "memory");     // keeps this a branch: full steps must not pay for the selects
+    }
+}
+
+// Scores of one 32-key block, S^T = K~ Q~^T, on their own (pipeline prologue).
+__device__ __forceinline__ void scores_block(const uint16_t* kblk, const FragLane& fl, const bf16x8 (&qf)[2][4],
+                                             floatx16 (&s)[2]) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int pos = 32 * ks + 16 * (v >> 3) + 8 * g + (v & 7);
-            if (pos >= nvalid) {
-                sacc[ks][0][v] = -INFINITY;
-                sacc[ks][1][v] = -INFINITY;
-            }
+    for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kblk + (fl.k ^ (16 * kk)));
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            floatx16 z;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], kk == 0 ? z : s[qb], 0, 0, 0);
         }
-    };
-    auto numerators = [&](int ks) {
-        float psum[2];
-        for (int attempt = 0;; ++attempt) {
-            exp_block(sacc[ks], c, m_ref, pb[ks], psum);
-            // wave-uniform test; written so that NaN (-inf - -inf before the first rebase) trips it
-            const bool calm = psum[0] <= kRebaseThreshold && psum[1] <= kRebaseThreshold;
-            // one rebase always suffices for finite inputs (every p of the block is <= 1 after it);
-            // the bound keeps the loop finite when the inputs hold NaN or infinities
-            if (__builtin_expect(__ballot(!calm) == 0ull, 1) || attempt == 1) break;
-            rebase_block(sacc[ks], c, m_ref, l_run, oacc);
+    }
+}
+
+__device__ __forceinline__ bf16x8 read_v_frag(const uint16_t* vp) {
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(DFA_LDS_PTR(short4v, vp));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(DFA_LDS_PTR(short4v, vp + 4 * kRowElems));
+    const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// Second product of one 32-key block on its own (pipeline epilogue).
+__device__ __forceinline__ void accumulate_block(const uint16_t* vblk, const FragLane& fl, const u32x4 (&pb)[2][2],
+                                                 floatx16 (&oacc)[2][2]) {
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const bf16x8 vf = read_v_frag(vblk + fl.v + 16 * st * kRowElems + 32 * db);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pb[qb][st]), oacc[db][qb], 0, 0, 0);
         }
-        l_run[0] += psum[0];
-        l_run[1] += psum[1];
+}
+
+// One pipeline beat (32 keys).  Three independent pieces of work are woven into one
+// instruction stream, so that the matrix cores and the vector ALU of the SIMD are busy at the
+// same time from within a single wave:
+//   matrix cores : S^T of the NEXT block (K at k_next -> s_next), and O^T += V~^T P^T of the
+//                  PREVIOUS block (V at v_prev, probabilities p_prev);
+//   vector ALU   : softmax numerators of the CURRENT block (s_cur -> p_cur, psum).
+// The stream is laid out slot by slot: one MFMA, then the exponent, exponential and rounding /
+// row-sum instructions of three different score pairs (a vector instruction that needs the
+// result of the one just before it stalls the wave, so each pair moves one stage per slot).
+// Scheduling fences keep the compiler from regrouping the slots.
+__device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_prev, const FragLane& fl,
+                                     const bf16x8 (&qf)[2][4], const floatx16 (&s_cur)[2], floatx16 (&s_next)[2],
+                                     const u32x4 (&p_prev)[2][2], u32x4 (&p_cur)[2][2], floatx16 (&oacc)[2][2],
+                                     float c, const float (&m_ref)[2], float (&psum)[2]) {
+    bf16x8 kf[2], vf[2];           // fragments of MFMA group r live in slot r & 1
+    float t[16][2];                // exponents, then exponentials, of score pair q
+    float a[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // two independent partial row sums per query block
+
+    auto load_group = [&](int r) {     // group r: d-step r of the scores, (d block r/2, 16-key step r%2) of the accumulation
+        kf[r & 1] = *reinterpret_cast<const bf16x8*>(k_next + (fl.k ^ (16 * r)));
+        vf[r & 1] = read_v_frag(v_prev + fl.v + 16 * (r & 1) * kRowElems + 32 * (r >> 1));
     };
-    // transposed V fragments: within a 16-lane group lane i supplies the address of
-    // V[R + i/4][C + 4*(i%4) ..] and receives V[R .. R+3][C + i]
-    const int i16 = lane & 15;
-    const uint16_t* vbase = vl + ((i16 >> 2) + 8 * g) * kRowElems + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-    auto accumulate = [&](int ks) {
+    auto mfma = [&](int k) {           // MFMA k of the beat: group r = k/4; scores for query block 0, 1, then accumulation for 0, 1
+        const int r = k >> 2, qb = k & 1;
+        if ((k & 2) == 0) {
+            floatx16 z;
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const uint16_t* vp = vbase + (32 * ks + 16 * st) * kRowElems + 32 * db;
-                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(DFA_LDS_PTR(short4v, vp));
-                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(DFA_LDS_PTR(short4v, vp + 4 * kRowElems));
-                const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pb[ks][qb][st]), oacc[db][qb], 0, 0, 0);
-            }
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[r & 1], qf[qb][r], r == 0 ? z : s_next[qb], 0, 0, 0);
+        } else {
+            const int db = r >> 1, st = r & 1;
+            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r & 1], __builtin_bit_cast(bf16x8, p_prev[qb][st]), oacc[db][qb], 0, 0, 0);
+        }
     };
 
-    scores(0);
-    if (nvalid < kKeyTile) mask_tail(0);
-    __builtin_amdgcn_sched_barrier(0);
-    scores(1);                             // matrix cores: block 1 scores | vector ALU: block 0 exponentials
-    if (nvalid < kKeyTile) mask_tail(1);
-    numerators(0);
-    __builtin_amdgcn_sched_barrier(0);
-    accumulate(0);                         // matrix cores: block 0 second product | vector ALU: block 1 exponentials
-    numerators(1);
-    __builtin_amdgcn_sched_barrier(0);
-    accumulate(1);
+    load_group(0);
+#pragma unroll
+    for (int m = 0; m < 18; ++m) {
+        // fragment reads run four slots ahead of their first MFMA
+        if (m >= 2 && m < 14 && ((m - 2) & 3) == 0) load_group(((m - 2) >> 2) + 1);
+        if (m >= 2 && m < 18) mfma(m - 2);
+        if (m < 16) {                                   // exponents of pair m
+            const int qb = m >> 3, v = 2 * (m & 7);
+            t[m][0] = fmaf(s_cur[qb][v], c, -m_ref[qb]);
+            t[m][1] = fmaf(s_cur[qb][v + 1], c, -m_ref[qb]);
+        }
+        if (m >= 1 && m < 17) {                         // exponentials of pair m - 1
+            t[m - 1][0] = __builtin_amdgcn_exp2f(t[m - 1][0]);
+            t[m - 1][1] = __builtin_amdgcn_exp2f(t[m - 1][1]);
+        }
+        if (m >= 2 && m < 18) {                         // pair m - 2: round into its B-operand slot, add to the row sums
+            const int q = m - 2, qb = q >> 3, pr = q & 7;
+            const bf16x2 w = {(__bf16)t[q][0], (__bf16)t[q][1]};
+            p_cur[qb][pr >> 2][pr & 3] = __builtin_bit_cast(uint32_t, w);
+            a[qb][0] += t[q][0];
+            a[qb][1] += t[q][1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    psum[0] = a[0][0] + a[0][1];
+    psum[1] = a[1][0] + a[1][1];
+}
+
+// The wave-uniform end of a beat: accept the numerators, or (rarely) move the reference
+// exponent and redo them.  oacc already holds every earlier block under the old reference.
+__device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur)[2][2], float c, float (&m_ref)[2],
+                                       float (&l_run)[2], floatx16 (&oacc)[2][2], float (&psum)[2]) {
+    // written so that NaN (-inf - -inf before the first rebase) trips the test
+    const bool calm = psum[0] <= kRebaseThreshold && psum[1] <= kRebaseThreshold;
+    if (__builtin_expect(__ballot(!calm) != 0ull, 0)) {
+        // one rebase always suffices for finite inputs (every p of the block is <= 1 after it)
+        rebase_block(s_cur, c, m_ref, l_run, oacc);
+        exp_block(s_cur, c, m_ref, p_cur, psum);
+    }
+    l_run[0] += psum[0];
+    l_run[1] += psum[1];
 }
 
 template <typename OutT>
@@ -338,14 +394,25 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
     // what this lane fetches in each copy (see CopyLane)
     CopyLane cl;
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int rho = 8 * (2 * wave + u) + (lane >> 3);                       // LDS row
-        cl.kpos[u] = (rho & 0x33) | ((rho & 4) << 1) | ((rho & 8) >> 1);        // sigma(rho)
-        cl.kchunk[u] = 16 * ((lane & 7) ^ k_swizzle(rho));
-        cl.vpos[u] = rho;
+    {
+        const int rho = 16 * wave + (lane >> 3);                                // LDS row of copy 0 (bit 3 clear)
+        cl.kpos = (rho & 0x33) | ((rho & 4) << 1);                              // sigma(rho)
+        cl.kchunk = 16 * ((lane & 7) ^ k_swizzle(rho));
+        cl.vpos = rho;
+        cl.vchunk = 16 * (lane & 7);
     }
-    cl.vchunk = 16 * (lane & 7);
+
+    // what this lane reads back as MFMA fragments
+    auto frag_lane = [](int ln) {
+        FragLane f;
+        const int jj = ln & 31, gg = ln >> 5, i16 = ln & 15;
+        f.k = jj * kRowElems + 8 * (gg ^ k_swizzle(jj));
+        // transposed V fragments: within a 16-lane group lane i supplies the address of
+        // V[R + i/4][C + 4*(i%4) ..] and receives V[R .. R+3][C + i]
+        f.v = ((i16 >> 2) + 8 * gg) * kRowElems + 16 * ((ln >> 4) & 1) + 4 * (i16 & 3);
+        return f;
+    };
+    const FragLane fl = frag_lane(lane);
 
     int n_steps = 0;
     for (int s = 0; s < tile.nseg; ++s)
@@ -355,7 +422,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     const uint32_t v_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &v_lds[0][0]);
     constexpr uint32_t kStageBytes = kStageElems * 2;
 
-    // first two stages on their way before anything else
+    // stage 0 on its way before anything else
     KeyCursor pf;
     pf.s = 0;
     pf.t = 0;
@@ -363,10 +430,6 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     KeyCursor cur = pf;
     issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr, v_lds_addr);
     cursor_next(pf, seg_lds, tile.nseg);
-    if (n_steps > 1) {
-        issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + kStageBytes, v_lds_addr + kStageBytes);
-        cursor_next(pf, seg_lds, tile.nseg);
-    }
 
     // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
     bf16x8 qf[2][4];
@@ -379,16 +442,27 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             for (int kk = 0; kk < 4; ++kk)
                 qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
         }
-        // pin the fragments here: the compiler then waits for these loads before the main loop
-        // and places no vector-memory wait of its own inside it (it cannot see the copies above,
-        // and a wait sized for these eight loads would drain the copy pipeline every step)
+        // pin the fragments here: the compiler then waits for these loads (and, as the counter
+        // is shared, for stage 0) before the main loop and places no vector-memory wait of its
+        // own inside it (it cannot see the copies, and a wait sized for these eight loads would
+        // drain the copy pipeline every step)
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[qb][kk]));
     }
+    wait_vmcnt<0>();
+    // stages 1 and 2 follow; from here on exactly two stages are in flight at every wait
+#pragma unroll
+    for (int s = 1; s <= 2; ++s)
+        if (s < n_steps) {
+            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + s * kStageBytes, v_lds_addr + s * kStageBytes);
+            cursor_next(pf, seg_lds, tile.nseg);
+        }
+    __syncthreads();           // stage 0 complete in LDS
 
-    const float c = p.scale * kLog2e;          // exponent scale: exp(s*x) = exp2(c*x)
+    // exponent scale, exp(s*x) = exp2(c*x); wave-uniform, so it is kept in a scalar register
+    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale * kLog2e)));
 
     floatx16 oacc[2][2];                       // [d block][query block], O^T layout
 #pragma unroll
@@ -406,28 +480,64 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
 
+    // Software pipeline over 32-key blocks (two per stage).  Entering trip s: s_a holds the
+    // scores of block 2s, p_b the probabilities of block 2s-1 (zero before the first block).
+    floatx16 s_a[2], s_b[2];
+    u32x4 p_a[2][2], p_b[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) p_b[qb][st] = u32x4{0u, 0u, 0u, 0u};
+    if (wave_live) scores_block(k_lds[0], fl, qf, s_a);
+
     int stage = 0;
-    for (int i = 0; i < n_steps; ++i) {
-        // stage i has landed once at most the 4 copies of stage i+1 are still outstanding
-        // (the Q loads were issued after the first two stages, so the first wait covers them)
-        if (i == 0 || i + 1 >= n_steps) wait_vmcnt<0>(); else wait_vmcnt<4>();
-        __syncthreads();       // every wave's share is in LDS, and everyone is done with stage i-1
-        if (i + 2 < n_steps) {
-            const int st2 = stage == 0 ? 2 : stage - 1;        // (stage + 2) % 3
-            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + st2 * kStageBytes, v_lds_addr + st2 * kStageBytes);
+    for (int s = 0; s < n_steps; ++s) {
+        const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+        const int stage_prev = stage == 0 ? kStages - 1 : stage - 1;
+        const int stage_next = stage == kStages - 1 ? 0 : stage + 1;
+        float psum[2];
+        if (wave_live) {
+            // beat 2s: scores of block 2s+1, accumulation of block 2s-1 (before the first block:
+            // zero probabilities against rows that are in LDS anyway), numerators of block 2s
+            if (nvalid < 32) mask_block(s_a, g, nvalid);
+            const uint16_t* v_prev = (s == 0 ? v_lds[0] : v_lds[stage_prev]) + 32 * kRowElems;
+            beat(k_lds[stage] + 32 * kRowElems, v_prev, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
+            settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
+        }
+        // stage s+1 has landed once at most the 4 copies of stage s+2 are still outstanding
+        if (s + 2 < n_steps) wait_vmcnt<4>(); else wait_vmcnt<0>();
+        __syncthreads();       // every wave's share of stage s+1 is in LDS, and everyone is done with stage s-1
+        if (s + 3 < n_steps) {
+            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + stage_prev * kStageBytes, v_lds_addr + stage_prev * kStageBytes);
             cursor_next(pf, seg_lds, tile.nseg);
         }
-        const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
-        if (wave_live) tile_step(k_lds[stage], v_lds[stage], qf, lane, nvalid, c, m_ref, l_run, oacc);
+        if (wave_live) {
+            // beat 2s+1: scores of block 2s+2 (past the last block: of whatever the next stage
+            // holds, never used), accumulation of block 2s, numerators of block 2s+1
+            if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
+            beat(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
+            settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
+        }
         cursor_next(cur, seg_lds, tile.nseg);
-        stage = stage == 2 ? 0 : stage + 1;
+        stage = stage_next;
+    }
+    // From here on the lane constants are worked out afresh, from a copy of the lane number the
+    // compiler cannot see through: carried across the loop they would cost it registers that
+    // the loop needs, and spills to scratch memory.
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    // accumulation of the last block
+    if (wave_live) {
+        const int stage_last = stage == 0 ? kStages - 1 : stage - 1;
+        accumulate_block(v_lds[stage_last] + 32 * kRowElems, frag_lane(lane_e), p_b, oacc);
     }
 
     // ---- epilogue: normalise, log-sum-exp, place each row at its own token (Eq. 3)
+    const int j_e = lane_e & 31, g_e = lane_e >> 5;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const int slot = wave * 64 + qb * 32 + j;
-        const float l_tot = l_run[qb] + wave_half_xchg(l_run[qb]);
+        const int slot = wave * 64 + qb * 32 + j_e;
+        const float l_tot = wave_half_sum(l_run[qb]);
         const float inv = 1.0f / l_tot;
         if (slot < tile.nrows) {
             const int64_t n = row_idx[slot];
@@ -436,10 +546,10 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq)
-                    store4<OutT>(op + 32 * db + 8 * vq + 4 * g,
+                    store4<OutT>(op + 32 * db + 8 * vq + 4 * g_e,
                                  oacc[db][qb][4 * vq] * inv, oacc[db][qb][4 * vq + 1] * inv,
                                  oacc[db][qb][4 * vq + 2] * inv, oacc[db][qb][4 * vq + 3] * inv);
-            if (p.lse && g == 0)
+            if (p.lse && g_e == 0)
                 p.lse[((int64_t)b * p.H + h) * p.N + n] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
         }
     }
