@@ -24,6 +24,69 @@ WORKLOAD = "throughput"
 MEASURED_HBM_TRAFFIC_BYTES = {"throughput": 748079104}
 
 
+HBM_PEAK_GBS = 8000.0               # MI355X HBM3E (published)
+
+
+def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
+    """Achieved HBM GB/s of the unfused stage entry points (algorithmic bytes / HIP-event time).
+
+    Algorithmic bytes per launch: gather 2*D*esize per kept row; placement D*esize*(1 + 1/r) per
+    token-head; merge nb*(4*D + 4) read + D*esize + 4 written per token-head.  The unmerged
+    branch launches are reported in TFLOP/s (they are the attention kernel on one branch).
+    """
+    Bsz, N, H, D = q.shape
+    esize = q.element_size()
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps            # ms
+
+    rows = []
+    for (w, r) in branches:
+        xg = binding.gather(k, w, r)
+        ms = timed(lambda: binding.gather(k, w, r, out=xg))
+        nbytes = 2 * Bsz * H * (N // r) * D * esize
+        rows.append({"kernel": "gather_kernel", "branch": [w, r], "ms": ms, "bytes": nbytes,
+                     "GB/s": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS})
+    for (w, r) in branches:
+        og = binding.gather(k, w, r)
+        placed = binding.scatter(og, N, w, r)
+        ms = timed(lambda: binding.scatter(og, N, w, r, out=placed))
+        nbytes = Bsz * N * H * D * esize + Bsz * H * (N // r) * D * esize
+        rows.append({"kernel": "scatter_kernel", "branch": [w, r], "ms": ms, "bytes": nbytes,
+                     "GB/s": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS})
+        del og
+    parts = []
+    for (w, r) in branches:
+        ob, lb = binding.forward_branch(q, k, v, w, r, scale)
+        ms = timed(lambda: binding.forward_branch(q, k, v, w, r, scale, out_b=ob, lse_b=lb))
+        fl = 4 * D * Bsz * H * N * w // (r * r)
+        rows.append({"kernel": "dfa_fwd_bf16_kernel<float> (one branch, unmerged)", "branch": [w, r], "ms": ms,
+                     "flops": fl, "TFLOP/s": fl / ms / 1e9})
+        parts.append((ob, lb))
+    out_b = torch.stack([p[0] for p in parts])
+    lse_b = torch.stack([p[1] for p in parts])
+    del parts
+    mo, ml = binding.merge(out_b, lse_b, q.dtype)
+    ms = timed(lambda: binding.merge(out_b, lse_b, q.dtype, out=mo, lse=ml))
+    nb = len(branches)
+    nbytes = Bsz * N * H * (nb * (4 * D + 4) + D * esize + 4)
+    rows.append({"kernel": "merge_kernel", "branches": nb, "ms": ms, "bytes": nbytes,
+                 "GB/s": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS})
+    unfused_ms = sum(r_["ms"] for r_ in rows if r_["kernel"].startswith("dfa_fwd")) + ms
+    return {"stages": rows, "hbm_peak_GB/s": HBM_PEAK_GBS, "steps": steps, "warmup": warmup,
+            "unfused_path_ms": unfused_ms,
+            "note": "unfused_path_ms = the three unmerged branch launches + merge; the fused dfa_forward does all of it in one launch"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -31,6 +94,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=WORKLOAD, help="name in synth.CONFIGS (default: throughput)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stages", action="store_true",
+                    help="time the stand-alone stage kernels (gather, placement, unmerged branches, merge) "
+                         "on the same workload and print their achieved HBM GB/s instead of the default line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
@@ -74,6 +140,10 @@ def main():
     out = torch.empty((Bsz, N, H, D), dtype=q.dtype, device="cuda")
     lse = torch.empty((Bsz, H, N), dtype=torch.float32, device="cuda")
     flops = synth.useful_flops(Bsz, H, N, D, branches)
+
+    if args.stages:
+        print(json.dumps(stage_report(binding, torch, q, k, v, branches, scale, args.steps, args.warmup)))
+        return
 
     for _ in range(args.warmup):
         binding.forward(q, k, v, branches, scale, out=out, lse=lse)

@@ -195,14 +195,16 @@ def forward_timed(q, k, v, branches, scale, iters, head_offsets=None, out=None, 
     return ms.value
 
 
-def forward_branch(q, k, v, w, r, scale, head_offsets=None):
+def forward_branch(q, k, v, w, r, scale, head_offsets=None, out_b=None, lse_b=None):
     """One unmerged branch: (out_b fp32 [B,N,H,D] zero on rows not kept, lse_b fp32 [B,H,N] -inf there)."""
     import torch
     for t, nm in ((q, "q"), (k, "k"), (v, "v")):
         _gpu(t, nm)
     B, N, H, D = q.shape
-    out_b = torch.empty((B, N, H, D), dtype=torch.float32, device=q.device)
-    lse_b = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    if out_b is None:
+        out_b = torch.empty((B, N, H, D), dtype=torch.float32, device=q.device)
+    if lse_b is None:
+        lse_b = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     _check(lib().dfa_forward_branch(
         ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
         _strides(q), _strides(k), _strides(v), B, H, N, D, _dtype_code(q), ctypes.c_float(scale),
@@ -211,14 +213,16 @@ def forward_branch(q, k, v, w, r, scale, head_offsets=None):
     return out_b, lse_b
 
 
-def merge(out_b, lse_b, dtype):
+def merge(out_b, lse_b, dtype, out=None, lse=None):
     """LSE merge of stacked branch results: out_b fp32 [nb,B,N,H,D], lse_b fp32 [nb,B,H,N]."""
     import torch
     _gpu(out_b, "out_b")
     _gpu(lse_b, "lse_b")
     nb, B, N, H, D = out_b.shape
-    out = torch.empty((B, N, H, D), dtype=dtype, device=out_b.device)
-    lse = torch.empty((B, H, N), dtype=torch.float32, device=out_b.device)
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=dtype, device=out_b.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=out_b.device)
     code = DFA_BF16 if dtype == torch.bfloat16 else DFA_F32
     _check(lib().dfa_merge(ctypes.c_void_p(out_b.data_ptr()), ctypes.c_void_p(lse_b.data_ptr()), nb, B, H, N, D,
                            code, ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()), _stream()),
@@ -226,23 +230,24 @@ def merge(out_b, lse_b, dtype):
     return out, lse
 
 
-def gather(x, w, r, head_offsets=None):
+def gather(x, w, r, head_offsets=None, out=None):
     """Kept rows of x [B, N, H, D] -> dense [B, H, N // r, D] (Eq. 1)."""
     import torch
     _gpu(x, "x")
     B, N, H, D = x.shape
-    xg = torch.empty((B, H, N // r, D), dtype=x.dtype, device=x.device)
+    xg = out if out is not None else torch.empty((B, H, N // r, D), dtype=x.dtype, device=x.device)
     _check(lib().dfa_gather(ctypes.c_void_p(x.data_ptr()), _strides(x), B, H, N, D, _dtype_code(x), Branch(w, r),
                             _i32_array(head_offsets), ctypes.c_void_p(xg.data_ptr()), _stream()), "dfa_gather")
     return xg
 
 
-def scatter(og, N, w, r, head_offsets=None):
+def scatter(og, N, w, r, head_offsets=None, out=None):
     """Dense [B, H, N // r, D] back to token positions [B, N, H, D], zero elsewhere (Eq. 3)."""
     import torch
     _gpu(og, "og")
     B, H, _, D = og.shape
-    out = torch.empty((B, N, H, D), dtype=og.dtype, device=og.device)
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=og.dtype, device=og.device)
     _check(lib().dfa_scatter(ctypes.c_void_p(og.data_ptr()), B, H, N, D, _dtype_code(og), Branch(w, r),
                              _i32_array(head_offsets), ctypes.c_void_p(out.data_ptr()), _stream()), "dfa_scatter")
     return out

@@ -29,12 +29,7 @@ struct DevicePlan {
 std::mutex g_mu;
 std::map<std::vector<int32_t>, DevicePlan> g_plans;
 
-int plan_order_mode() {
-    // measurement knob, read when a plan is built: DFA_PLAN_ORDER = 0, 1 or 2 (default)
-    const char* e = std::getenv("DFA_PLAN_ORDER");
-    if (e && e[0] >= '0' && e[0] <= '2' && e[1] == 0) return e[0] - '0';
-    return 2;
-}
+constexpr int kPlanOrder = 2;   // launch order of build_plan (see dfa_plan.cpp)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -43,8 +38,7 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
              const int32_t* offsets, DevicePlan* out) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return DFA_ERR_LAUNCH;
-    const int mode = plan_order_mode();
-    std::vector<int32_t> key = {device, B, H, N, nb, mode, offsets ? 1 : 0};
+    std::vector<int32_t> key = {device, B, H, N, nb, offsets ? 1 : 0};
     for (int x = 0; x < nb; ++x) {
         key.push_back(br[x].w);
         key.push_back(br[x].r);
@@ -58,7 +52,7 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
         return DFA_OK;
     }
     HostPlan hp;
-    build_plan(B, H, N, br, nb, offsets, mode, &hp);
+    build_plan(B, H, N, br, nb, offsets, kPlanOrder, &hp);
     if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
     const size_t b_tiles = align256(hp.tiles.size() * sizeof(Tile));
     const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
@@ -99,6 +93,13 @@ int check_common(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt) {
     if (B <= 0 || H <= 0 || N <= 0 || D != DFA_HEAD_DIM) return DFA_ERR_SHAPE;
     if (dt != DFA_BF16 && dt != DFA_F32) return DFA_ERR_DTYPE;
     if ((int64_t)B * H * N > ((int64_t)1 << 40)) return DFA_ERR_TOO_LARGE;
+    return DFA_OK;
+}
+
+// The stand-alone stage kernels carry b (and h) in grid.y / grid.z and index one image with
+// 32-bit counters.
+int check_stage_grid(int32_t B, int32_t H, int32_t N) {
+    if (B > 65535 || H > 65535 || (int64_t)N * H * 16 >= ((int64_t)1 << 31)) return DFA_ERR_TOO_LARGE;
     return DFA_OK;
 }
 
@@ -226,7 +227,9 @@ int dfa_merge(const float* out_b, const float* lse_b, int32_t nb, int32_t B, int
               int32_t D, dfa_dtype_t dt, void* out, float* lse, void* stream) {
     if (!out_b || !lse_b || !out) return DFA_ERR_NULL;
     if (nb < 1 || nb > DFA_MAX_BRANCHES) return DFA_ERR_BRANCHES;
-    const int rc = check_common(B, H, N, D, dt);
+    int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    rc = check_stage_grid(B, H, N);
     if (rc != DFA_OK) return rc;
     if (reinterpret_cast<uintptr_t>(out_b) % 16 || reinterpret_cast<uintptr_t>(out) % 16) return DFA_ERR_ALIGN;
     return launch_merge(out_b, lse_b, nb, B, H, N, dt == DFA_BF16, out, lse,
@@ -239,6 +242,8 @@ int dfa_gather(const void* x, dfa_strides_t sx, int32_t B, int32_t H, int32_t N,
     int rc = check_common(B, H, N, D, dt);
     if (rc != DFA_OK) return rc;
     if (br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    rc = check_stage_grid(B, H, N);
+    if (rc != DFA_OK) return rc;
     HeadOffsets offs;
     rc = make_offsets(head_offsets, H, br.r, &offs);
     if (rc != DFA_OK) return rc;
@@ -253,6 +258,8 @@ int dfa_scatter(const void* og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
     int rc = check_common(B, H, N, D, dt);
     if (rc != DFA_OK) return rc;
     if (br.r < 1 || br.w < br.r || br.w > N || N % br.w || br.w % br.r) return DFA_ERR_SHAPE;
+    rc = check_stage_grid(B, H, N);
+    if (rc != DFA_OK) return rc;
     HeadOffsets offs;
     rc = make_offsets(head_offsets, H, br.r, &offs);
     if (rc != DFA_OK) return rc;
@@ -270,7 +277,7 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
     if (rc != DFA_OK) return rc;
     try {
         HostPlan hp;
-        build_plan(B, H, N, branches, nb, head_offsets, plan_order_mode(), &hp);
+        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, &hp);
         *n_tiles = (int32_t)hp.tiles.size();
         *n_rows = (int32_t)hp.rows.size();
         *n_segs = (int32_t)hp.segs.size();
