@@ -77,6 +77,35 @@ def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
     assert _fwd_rc(B, sq=B.Strides(64 * 2 * 64, 2 * 64 + 4, 64)) == -5
 
 
+def test_stage_entry_points_reject_bad_arguments_before_any_gpu_work(B):
+    """dfa_gather / dfa_scatter / dfa_merge: argument errors are found on the host (fake, aligned pointers)."""
+    L, vp, fake = B.lib(), ctypes.c_void_p, 0x10000
+    st = B.Strides(64 * 2 * 64, 2 * 64, 64)
+
+    def gather(x=fake, xg=fake, Bsz=1, H=2, N=64, D=64, dt=0, br=(16, 2), offs=None):
+        return L.dfa_gather(vp(x), st, Bsz, H, N, D, dt, B.Branch(*br), B._i32_array(offs), vp(xg), None)
+
+    def scatter(og=fake, out=fake, Bsz=1, H=2, N=64, D=64, dt=0, br=(16, 2), offs=None):
+        return L.dfa_scatter(vp(og), Bsz, H, N, D, dt, B.Branch(*br), B._i32_array(offs), vp(out), None)
+
+    def merge(ob=fake, lb=fake, nb=2, Bsz=1, H=2, N=64, D=64, dt=0, out=fake, lse=fake):
+        return L.dfa_merge(vp(ob), vp(lb), nb, Bsz, H, N, D, dt, vp(out), vp(lse), None)
+
+    assert gather(x=None) == -1 and gather(xg=None) == -1
+    assert gather(D=32) == -2 and gather(br=(48, 2)) == -2 and gather(br=(16, 3)) == -2
+    assert gather(offs=[0, 2]) == -2
+    assert gather(dt=5) == -4
+    assert gather(x=0x10008) == -5
+    assert gather(Bsz=70000) == -7                           # b rides on a grid dimension
+    assert scatter(og=None) == -1 and scatter(out=None) == -1
+    assert scatter(br=(128, 1)) == -2 and scatter(dt=9) == -4 and scatter(out=0x10004) == -5
+    assert scatter(H=70000, br=(16, 1)) == -7
+    assert merge(ob=None) == -1 and merge(out=None) == -1
+    assert merge(nb=0) == -3 and merge(nb=9) == -3
+    assert merge(D=128) == -2 and merge(dt=3) == -4 and merge(ob=0x10004) == -5
+    assert merge(N=1 << 22, H=64) == -7                      # one image no longer fits 32-bit counters
+
+
 def _expected_key_sets(N, h, branches, offs):
     """row -> sorted list of (first key, stride, count), from the definition."""
     exp = {}

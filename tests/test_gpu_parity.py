@@ -157,6 +157,80 @@ def test_bf16_eight_branches_and_no_lse(B, oracle):
     assert none is None and bool((out2 == out).all())
 
 
+@pytest.mark.parametrize("count,r", [(1, 1), (2, 1), (31, 1), (32, 1), (33, 1), (63, 2), (64, 1), (65, 3),
+                                     (95, 1), (96, 2), (97, 1), (128, 1), (129, 2), (257, 1)])
+def test_bf16_key_counts_around_the_pipeline_beats(B, oracle, count, r):
+    """Segments of `count` kept keys: one key (a row attends only itself), and counts just below,
+    at and above the 32-key beat and the 64-key stage of the kernel's pipeline, with a second,
+    coarser branch on top so that two key lists of ragged length are walked back to back."""
+    w = count * r
+    N, H = 4 * w, 3
+    branches = [(w, r), (2 * w, 2 * r)]
+    (q, k, v), ex = make_qkv(300 + count, 2, N, H, 64, "bf16")
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
+    _check_bf16(out, lse, o_ref, l_ref, f"bf16 count {count} r {r}")
+    out1, lse1 = B.forward(q, k, v, branches[:1], 0.125)
+    o1, l1 = oracle.forward(*ex, branches[:1], 0.125)
+    _check_bf16(out1, lse1, o1, l1, f"bf16 count {count} r {r}, one branch")
+
+
+def test_bf16_reference_exponent_moves_when_logits_keep_growing(B, oracle):
+    """Keys ordered so that logits grow along every key list (and jump between lists): the
+    reference exponent of the online softmax has to move many times, also late in the walk,
+    and the accumulator is rescaled each time.  Keys with falling logits follow in the second
+    head, where it must never move after the first block."""
+    import torch
+    from paper_2403_09195_amd import synth
+    Bsz, N, H, D = 1, 1024, 2, 64
+    branches = [(512, 1), (1024, 2)]
+    st, ex = synth.qkv(301, Bsz, N, H, D, "bf16")
+    q, k, v = (np.array(a, dtype=np.float64) for a in ex)
+    q[:] = np.abs(q)                                   # q.k grows with the ramp applied to k below
+    ramp = np.linspace(0.2, 6.0, N)[None, :, None, None]
+    k = np.abs(k) * ramp
+    k[:, :, 1] = k[:, ::-1, 1]                         # head 1: falling
+    def to_bf16(a):
+        t = torch.from_numpy(a.astype(np.float32)).bfloat16()
+        return t.cuda(), t.float().numpy().astype(np.float64)
+    (qd, qe), (kd, ke), (vd, ve) = to_bf16(q), to_bf16(k), to_bf16(v)
+    out, lse = B.forward(qd, kd, vd, branches, 0.125)
+    o_ref, l_ref = oracle.forward(qe, ke, ve, branches, 0.125)
+    assert l_ref.max() > 40.0                          # far beyond what one fixed exponent could carry in bf16 sums
+    mx, mean = error_stats(to_f64(out), o_ref)
+    le = check_lse(to_f64(lse), l_ref, atol=0.0, rtol=1e-4)
+    print(f"[growing logits] out max-abs {mx:.3e} mean-abs {mean:.3e} lse rel {le:.3e}", flush=True)
+    assert mx <= BF16_MAX and mean <= BF16_MEAN
+
+
+def test_bf16_side_stream_and_plan_release(B, oracle):
+    """The launch goes to the caller's stream; a released plan cache is rebuilt on the next call."""
+    import torch
+    Bsz, N, H, D = 2, 768, 3, 64
+    branches = [(256, 1), (768, 3)]
+    (q, k, v), ex = make_qkv(302, Bsz, N, H, D, "bf16")
+    out0, lse0 = B.forward(q, k, v, branches, 0.125)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
+    _check_bf16(out0, lse0, o_ref, l_ref, "default stream")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        out1, lse1 = B.forward(q, k, v, branches, 0.125)
+    side.synchronize()
+    assert bool((out1 == out0).all()) and bool((lse1 == lse0).all())
+    torch.cuda.synchronize()
+    B.release_plans()
+    out2, lse2 = B.forward(q, k, v, branches, 0.125)
+    assert bool((out2 == out0).all()) and bool((lse2 == lse0).all())
+    # another shape in between, then the first one again (two cached plans)
+    (q3, k3, v3), ex3 = make_qkv(303, 1, 256, 2, D, "bf16")
+    out3, lse3 = B.forward(q3, k3, v3, [(128, 2)], 0.125)
+    o3, l3 = oracle.forward(*ex3, [(128, 2)], 0.125)
+    _check_bf16(out3, lse3, o3, l3, "second shape")
+    out4, _ = B.forward(q, k, v, branches, 0.125)
+    assert bool((out4 == out0).all())
+
+
 def test_bf16_reads_packed_qkv_through_strides(B, oracle):
     import torch
     from paper_2403_09195_amd import synth
