@@ -154,3 +154,32 @@ def forward_rows(q, k, v, branches, scale, bhn, head_offsets=None):
     if rc != 0:
         raise ValueError("dfa_oracle_forward_rows: bad arguments")
     return out, lse
+
+
+# ---------------------------------------------------------------------------------------------
+# The steps either side of the operator inside one encoder layer (the "encoder attention
+# stack" workload: QKV projection 768 -> 2304, dilated attention, output projection 768 -> 768;
+# no bias, residual or normalisation).  The paper names these projections only as part of the
+# ViT encoder's self-attention blocks (section 3.1 / 4.4); the feature order of the fused QKV
+# output is this build's reading: feature f = t*E + h*D + d with t = 0, 1, 2 for q, k, v.
+
+def linear(x, w):
+    """y = x . w^T in fp64: x [..., K], w [N, K] (one weight row per output feature) -> [..., N]."""
+    x, w = _f64(x), _f64(w)
+    assert x.shape[-1] == w.shape[1]
+    return np.matmul(x, w.T)
+
+
+def attention_layer(x, w_qkv, w_o, H, branches, scale, head_offsets=None):
+    """One layer of the stack: x [B, N, E] -> (y [B, N, E], qkv [B, N, 3, H, D], attn [B, N, H, D]).
+
+    qkv = x . w_qkv^T split as [3][H][D]; attn = dilated attention of (q, k, v); y = attn . w_o^T.
+    """
+    x = _f64(x)
+    B, N, E = x.shape
+    D = E // H
+    assert w_qkv.shape == (3 * E, E) and w_o.shape == (E, E) and H * D == E
+    qkv = linear(x, w_qkv).reshape(B, N, 3, H, D)
+    attn, _ = forward(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], branches, scale, head_offsets)
+    y = linear(attn.reshape(B, N, E), w_o)
+    return y, qkv, attn

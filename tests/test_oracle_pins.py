@@ -310,3 +310,48 @@ def test_small_full_forward_consistent_with_rows_and_scale_one(oracle):
     for x, (w, r) in enumerate(branches):
         ob, lb = oracle.branch(q, k, v, w, r, 1.0)
         assert np.array_equal(ob, bo[x]) and np.array_equal(lb, bl[x])
+
+
+# ---------------------------------------------------------------- projections around the operator
+def test_linear_matches_a_triple_loop_and_identity(oracle):
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((3, 5, 7))
+    w = rng.standard_normal((4, 7))
+    y = oracle.linear(x, w)
+    ref = np.zeros((3, 5, 4))
+    for a in range(3):
+        for b in range(5):
+            for n in range(4):
+                acc = 0.0
+                for k in range(7):
+                    acc += x[a, b, k] * w[n, k]          # weight row n produces output feature n
+                ref[a, b, n] = acc
+    assert np.abs(y - ref).max() < 1e-13
+    assert np.array_equal(oracle.linear(x, np.eye(7)), x)
+    # a transposed weight would fail this: output feature 0 must read weight ROW 0
+    w2 = np.zeros((4, 7)); w2[0, :] = 1.0
+    assert np.allclose(oracle.linear(x, w2)[..., 0], x.sum(-1)) and np.all(oracle.linear(x, w2)[..., 1:] == 0)
+
+
+def test_attention_layer_reduces_to_the_operator_with_identity_projections(oracle):
+    """w_qkv = [I; I; I], w_o = I: the layer is the dilated attention of q = k = v = x split into heads,
+    which the pins above already fix; a wrong q/k/v or head order in the split shows with the
+    second weight set, where the three blocks and the heads are scaled differently."""
+    rng = np.random.default_rng(12)
+    B, N, H, D = 2, 32, 2, 4
+    E = H * D
+    x = rng.standard_normal((B, N, E))
+    branches = [(8, 1), (16, 2)]
+    eye = np.eye(E)
+    y, qkv, attn = oracle.attention_layer(x, np.concatenate([eye, eye, eye]), eye, H, branches, 0.5)
+    xh = x.reshape(B, N, H, D)
+    ref, _ = oracle.forward(xh, xh, xh, branches, 0.5)
+    assert np.abs(y - ref.reshape(B, N, E)).max() < 1e-13
+    assert np.array_equal(qkv[:, :, 1], xh)
+    # q scaled by 2, k by 3, v by 5, and head 1 of v additionally by 7; output projection permutes features
+    sv = np.diag(np.concatenate([np.full(D, 5.0), np.full(D, 35.0)]))
+    perm = np.eye(E)[::-1]
+    y2, _, _ = oracle.attention_layer(x, np.concatenate([2 * eye, 3 * eye, sv]), perm, H, branches, 0.5)
+    vh = xh * np.array([5.0, 35.0])[None, None, :, None]
+    ref2, _ = oracle.forward(2 * xh, 3 * xh, vh, branches, 0.5)
+    assert np.abs(y2 - ref2.reshape(B, N, E)[..., ::-1]).max() < 1e-12
