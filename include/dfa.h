@@ -155,6 +155,40 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branc
                       int32_t *n_segs, int32_t *n_items, int32_t *tiles, int32_t *rows,
                       int32_t *segs, int32_t *items);
 
+/*
+ * Projection either side of the operator inside an encoder layer (the ViT self-attention
+ * block the paper's encoder is built from, section 3.1): y = x . w^T, one weight ROW per
+ * output feature, no bias.  bf16 operands on the matrix cores, fp32 accumulation, y rounded
+ * to bf16.
+ *   x device bf16 [M][K] with row pitch ldx, w device bf16 [N][K] with row pitch ldw,
+ *   y device bf16 [M][N] with row pitch ldy (pitches in elements, each a multiple of 8;
+ *   base pointers 16-byte aligned).  M % 128 == 0, N % 128 == 0, K % 32 == 0, else
+ *   DFA_ERR_SHAPE.  y must not overlap x or w.  Asynchronous on `stream`.
+ */
+int dfa_linear(const void *x, const void *w, void *y, int64_t M, int32_t N, int32_t K,
+               int64_t ldx, int64_t ldw, int64_t ldy, void *stream);
+
+/*
+ * `layers` encoder attention layers back to back (the "encoder attention stack" workload):
+ * per layer  qkv = x_l . w_qkv[l]^T  (features ordered [3][H][D]: q heads, k heads, v heads),
+ * attn = dfa_forward(q, k, v read in place from qkv through strides),  x_{l+1} = attn . w_o[l]^T.
+ * No bias, residual or normalisation.  E = H * D.
+ *   x        device bf16 [B][N][E], read only
+ *   w_qkv    device bf16 [layers][3E][E];  w_o  device bf16 [layers][E][E]
+ *   qkv_ws   device bf16 [B][N][3][H][D]   workspace, holds the last layer's qkv on return
+ *   attn_ws  device bf16 [B][N][H][D]      workspace, holds the last layer's attention output
+ *   y        device bf16 [B][N][E]         x_layers; also used for every intermediate x_l
+ *                                          (y may be the same buffer as x: x is then overwritten)
+ *   branches, head_offsets, scale          as in dfa_forward
+ * (B * N) % 128 == 0 and E % 128 == 0 are required (DFA_ERR_SHAPE otherwise); D must be 64.
+ * Three launches per layer on `stream`, nothing else; allocates only what dfa_forward's plan
+ * cache allocates on first use.
+ */
+int dfa_encoder_stack(const void *x, const void *w_qkv, const void *w_o, int32_t layers,
+                      int32_t B, int32_t H, int32_t N, int32_t D, float scale,
+                      const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
+                      void *qkv_ws, void *attn_ws, void *y, void *stream);
+
 /* Frees every cached launch plan of every device.  Synchronises the devices involved. */
 int dfa_release_plans(void);
 

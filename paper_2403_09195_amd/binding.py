@@ -18,7 +18,7 @@ DFA_MAX_BRANCHES = 8
 EXPORTS = [
     "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_forward",
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
-    "dfa_release_plans", "dfa_forward_timed",
+    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack",
 ]
 
 
@@ -77,6 +77,10 @@ def lib():
         L.dfa_scatter.argtypes = [vp, i32, i32, i32, i32, ctypes.c_int, Branch, _i32p, vp, vp]
         L.dfa_plan_describe.argtypes = [i32, i32, i32, ctypes.POINTER(Branch), i32, _i32p,
                                         _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p]
+        i64 = ctypes.c_int64
+        L.dfa_linear.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
+        L.dfa_encoder_stack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, ctypes.POINTER(Branch), i32,
+                                        _i32p, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "dfa_error_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -251,6 +255,53 @@ def scatter(og, N, w, r, head_offsets=None, out=None):
     _check(lib().dfa_scatter(ctypes.c_void_p(og.data_ptr()), B, H, N, D, _dtype_code(og), Branch(w, r),
                              _i32_array(head_offsets), ctypes.c_void_p(out.data_ptr()), _stream()), "dfa_scatter")
     return out
+
+
+def linear(x, w, out=None):
+    """y = x . w^T (bf16): x [..., K] with contiguous rows, w [N, K]; one weight row per output feature."""
+    import torch
+    _gpu(x, "x")
+    _gpu(w, "w")
+    K = x.shape[-1]
+    M = x.numel() // K
+    Nf = w.shape[0]
+    if x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16:
+        raise TypeError("linear: bf16 tensors expected")
+    if not x.is_contiguous() or w.stride(1) != 1 or w.shape[1] != K:
+        raise ValueError("linear: x must be contiguous and w [N, K] with contiguous rows")
+    y = out if out is not None else torch.empty(x.shape[:-1] + (Nf,), dtype=torch.bfloat16, device=x.device)
+    _check(lib().dfa_linear(ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w.data_ptr()), ctypes.c_void_p(y.data_ptr()),
+                            M, Nf, K, K, w.stride(0), y.stride(-2) if y.dim() > 1 else Nf, _stream()), "dfa_linear")
+    return y
+
+
+def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, workspace=None):
+    """`layers` attention layers back to back: x [B, N, E] bf16, w_qkv [layers, 3E, E], w_o [layers, E, E].
+
+    Returns (y [B, N, E], qkv of the last layer [B, N, 3, H, D], attention output of the last layer
+    [B, N, H, D]).  `workspace` = (qkv, attn, y) tensors to reuse."""
+    import torch
+    for t, nm in ((x, "x"), (w_qkv, "w_qkv"), (w_o, "w_o")):
+        _gpu(t, nm)
+        if t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise TypeError(f"encoder_stack: {nm} must be a contiguous bf16 tensor")
+    B, N, E = x.shape
+    layers = w_qkv.shape[0]
+    D = E // H
+    if tuple(w_qkv.shape) != (layers, 3 * E, E) or tuple(w_o.shape) != (layers, E, E) or H * D != E:
+        raise ValueError("encoder_stack: weight shapes do not match x")
+    if workspace is None:
+        workspace = (torch.empty((B, N, 3, H, D), dtype=torch.bfloat16, device=x.device),
+                     torch.empty((B, N, H, D), dtype=torch.bfloat16, device=x.device),
+                     torch.empty((B, N, E), dtype=torch.bfloat16, device=x.device))
+    qkv, attn, y = workspace
+    br, nb = _branches(branches)
+    vp = ctypes.c_void_p
+    _check(lib().dfa_encoder_stack(vp(x.data_ptr()), vp(w_qkv.data_ptr()), vp(w_o.data_ptr()), layers, B, H, N, D,
+                                   ctypes.c_float(scale), br, nb, _i32_array(head_offsets),
+                                   vp(qkv.data_ptr()), vp(attn.data_ptr()), vp(y.data_ptr()), _stream()),
+           "dfa_encoder_stack")
+    return y, qkv, attn
 
 
 def plan_describe(B, H, N, branches, head_offsets=None):

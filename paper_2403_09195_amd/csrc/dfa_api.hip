@@ -268,6 +268,52 @@ int dfa_scatter(const void* og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
                           static_cast<hipStream_t>(stream)) == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
 }
 
+int dfa_linear(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
+               int64_t ldx, int64_t ldw, int64_t ldy, void* stream) {
+    if (!x || !w || !y) return DFA_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || M % 128 || N % 128 || K % 32) return DFA_ERR_SHAPE;
+    if (ldx < K || ldw < K || ldy < N) return DFA_ERR_SHAPE;
+    if (ldx % 8 || ldw % 8 || ldy % 8 || reinterpret_cast<uintptr_t>(x) % 16 ||
+        reinterpret_cast<uintptr_t>(w) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return DFA_ERR_ALIGN;
+    // lane offsets inside an 8-row group are 32-bit; tiles are counted in 32 bits
+    if (ldx >= ((int64_t)1 << 26) || ldw >= ((int64_t)1 << 26) || (M / 128) * (int64_t)(N / 128) >= ((int64_t)1 << 30))
+        return DFA_ERR_TOO_LARGE;
+    return launch_linear_bf16(x, w, y, M, N, K, ldx, ldw, ldy, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
+int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t layers,
+                      int32_t B, int32_t H, int32_t N, int32_t D, float scale,
+                      const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                      void* qkv_ws, void* attn_ws, void* y, void* stream) {
+    if (!x || !w_qkv || !w_o || !qkv_ws || !attn_ws || !y) return DFA_ERR_NULL;
+    if (layers < 1) return DFA_ERR_SHAPE;
+    int rc = check_common(B, H, N, D, DFA_BF16);
+    if (rc != DFA_OK) return rc;
+    const int64_t E = (int64_t)H * D, M = (int64_t)B * N;
+    if (M % 128 || E % 128) return DFA_ERR_SHAPE;
+    const uint16_t* wq = static_cast<const uint16_t*>(w_qkv);
+    const uint16_t* wo = static_cast<const uint16_t*>(w_o);
+    const uint16_t* qkv = static_cast<const uint16_t*>(qkv_ws);
+    // q, k, v of token (b, n), head h live at qkv[((b*N + n)*3 + t)*E + h*D ..]
+    const dfa_strides_t sq = {(int64_t)N * 3 * E, 3 * E, D};
+    try {
+        for (int l = 0; l < layers; ++l) {
+            rc = dfa_linear(l == 0 ? x : y, wq + (int64_t)l * 3 * E * E, qkv_ws, M, (int32_t)(3 * E), (int32_t)E,
+                            E, E, 3 * E, stream);
+            if (rc != DFA_OK) return rc;
+            rc = forward_impl(qkv, qkv + E, qkv + 2 * E, sq, sq, sq, B, H, N, D, DFA_BF16, scale, branches, nb,
+                              head_offsets, attn_ws, false, nullptr, stream);
+            if (rc != DFA_OK) return rc;
+            rc = dfa_linear(attn_ws, wo + (int64_t)l * E * E, y, M, (int32_t)E, (int32_t)E, E, E, E, stream);
+            if (rc != DFA_OK) return rc;
+        }
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+    return DFA_OK;
+}
+
 int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
                       const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
                       int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* items) {

@@ -53,6 +53,8 @@ __device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o
 // Launchers (defined in the .hip files); every one returns the hipError_t of the launch.
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
+hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
+                              int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st);
 hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,
                             int32_t* d_idx, hipStream_t st);
 hipError_t launch_gather(const void* x, int64_t sb, int64_t sn, int64_t sh, int32_t B, int32_t H,
