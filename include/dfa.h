@@ -162,7 +162,7 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branc
  * to bf16.
  *   x device bf16 [M][K] with row pitch ldx, w device bf16 [N][K] with row pitch ldw,
  *   y device bf16 [M][N] with row pitch ldy (pitches in elements, each a multiple of 8;
- *   base pointers 16-byte aligned).  M % 128 == 0, N % 128 == 0, K % 32 == 0, else
+ *   base pointers 16-byte aligned).  M % 256 == 0, N % 128 == 0, K % 64 == 0, else
  *   DFA_ERR_SHAPE.  y must not overlap x or w.  Asynchronous on `stream`.
  */
 int dfa_linear(const void *x, const void *w, void *y, int64_t M, int32_t N, int32_t K,
@@ -180,7 +180,7 @@ int dfa_linear(const void *x, const void *w, void *y, int64_t M, int32_t N, int3
  *   y        device bf16 [B][N][E]         x_layers; also used for every intermediate x_l
  *                                          (y may be the same buffer as x: x is then overwritten)
  *   branches, head_offsets, scale          as in dfa_forward
- * (B * N) % 128 == 0 and E % 128 == 0 are required (DFA_ERR_SHAPE otherwise); D must be 64.
+ * (B * N) % 256 == 0 and E % 128 == 0 are required (DFA_ERR_SHAPE otherwise); D must be 64.
  * Three launches per layer on `stream`, nothing else; allocates only what dfa_forward's plan
  * cache allocates on first use.
  */

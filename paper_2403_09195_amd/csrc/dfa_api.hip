@@ -271,12 +271,12 @@ int dfa_scatter(const void* og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
 int dfa_linear(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                int64_t ldx, int64_t ldw, int64_t ldy, void* stream) {
     if (!x || !w || !y) return DFA_ERR_NULL;
-    if (M <= 0 || N <= 0 || K <= 0 || M % 128 || N % 128 || K % 32) return DFA_ERR_SHAPE;
+    if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 128 || K % 64) return DFA_ERR_SHAPE;
     if (ldx < K || ldw < K || ldy < N) return DFA_ERR_SHAPE;
     if (ldx % 8 || ldw % 8 || ldy % 8 || reinterpret_cast<uintptr_t>(x) % 16 ||
         reinterpret_cast<uintptr_t>(w) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return DFA_ERR_ALIGN;
     // lane offsets inside an 8-row group are 32-bit; tiles are counted in 32 bits
-    if (ldx >= ((int64_t)1 << 26) || ldw >= ((int64_t)1 << 26) || (M / 128) * (int64_t)(N / 128) >= ((int64_t)1 << 30))
+    if (ldx >= ((int64_t)1 << 26) || ldw >= ((int64_t)1 << 26) || (M / 256) * (int64_t)(N / 128) >= ((int64_t)1 << 30))
         return DFA_ERR_TOO_LARGE;
     return launch_linear_bf16(x, w, y, M, N, K, ldx, ldw, ldy, static_cast<hipStream_t>(stream)) == hipSuccess
                ? DFA_OK : DFA_ERR_LAUNCH;
@@ -291,7 +291,7 @@ int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t
     int rc = check_common(B, H, N, D, DFA_BF16);
     if (rc != DFA_OK) return rc;
     const int64_t E = (int64_t)H * D, M = (int64_t)B * N;
-    if (M % 128 || E % 128) return DFA_ERR_SHAPE;
+    if (M % 256 || E % 128) return DFA_ERR_SHAPE;
     const uint16_t* wq = static_cast<const uint16_t*>(w_qkv);
     const uint16_t* wo = static_cast<const uint16_t*>(w_o);
     const uint16_t* qkv = static_cast<const uint16_t*>(qkv_ws);

@@ -3,36 +3,39 @@
 // projection after it): y = x . w^T, bf16 operands on the gfx950 matrix cores, fp32
 // accumulation, result rounded to bf16 (nearest even).
 //
-// One workgroup of 4 waves owns a BM x BN tile of y (256 x 128, or 128 x 128 when that fills
-// the chip more evenly) and walks K in steps of 32.  Both operand tiles have their K elements
-// contiguous in memory (x rows and w rows), so both go global -> LDS as 64-byte rows
-// (global_load_lds, 16 bytes per lane, no staging registers) into a ring of three stages, two
-// in flight while the third is consumed, with the 16-byte chunks of a row XOR-swizzled so that
-// the fragment reads are free of bank conflicts, and both are read back as 16-byte MFMA
-// fragments.  Two workgroups share a CU (72 KB of LDS each), so that one's epilogue (the
-// stores of its tile, a quarter of the launch if nothing overlaps them) runs under the other's
-// matrix work.
+// One workgroup of 8 waves owns a 256 x BN tile of y (BN = 256 or 128) and walks K in steps
+// of 64.  Both operand tiles have their K elements contiguous in memory (x rows and w rows),
+// so both go global -> LDS as 128-byte rows (global_load_lds, 16 bytes per lane, no staging
+// registers) into two alternating stages, with the 16-byte chunks of a row XOR-swizzled so
+// that the fragment reads are free of bank conflicts, and both are read back as 16-byte MFMA
+// fragments.  What limits the kernel is the byte rate of the CU's vector memory path (copies in,
+// results out), so the tile is as large as LDS allows and the results leave as whole 128-byte
+// lines.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16): A operand = 32 weight rows (output
 // features) x 16 k, B operand = 16 k x 32 x-rows.  The result then has one x-row (one row of
-// y) per lane and 4 consecutive output features in 4 consecutive registers, which the
-// epilogue stores as 8-byte pieces.  A wave computes BM/2 rows x BN/2 features.
+// y) per lane and 4 consecutive output features in 4 consecutive registers.  A wave computes
+// 128 rows x BN/4 features: per 16 k it reads 4 + BN/128 fragments and issues 4 * BN/128 MFMAs.
+// Epilogue: each wave rounds its results to bf16, lays them out row-major in its own piece of
+// LDS (the stages are free by then) and stores them 16 bytes per lane, eight lanes to a row.
 #include "dfa_device.h"
 
 namespace dfa {
 
 namespace {
 
-constexpr int kLinBK = 32;                 // k elements per stage: one 64-byte LDS row
-constexpr int kLinStages = 3;
+constexpr int kLinBM = 256;                // rows of y per workgroup
+constexpr int kLinBK = 64;                 // k elements per stage: one 128-byte LDS row
+constexpr int kLinStages = 2;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define DFA_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-// 16-byte chunk swizzle: chunk c (0..3) of LDS row rho sits at chunk c ^ swizzle(rho).  Sixteen
+// 16-byte chunk swizzle: chunk c of LDS row rho sits at chunk c ^ swizzle(rho).  Sixteen
 // consecutive rows then spread one chunk column over all 64 banks.
-__device__ __forceinline__ int lin_swizzle(int rho) { return (rho >> 2) & 3; }
+__device__ __forceinline__ int lin_swizzle(int rho) { return (rho >> 1) & 7; }
 
 template <int N>
 __device__ __forceinline__ void lin_wait_vmcnt() {
@@ -57,17 +60,18 @@ __device__ __forceinline__ const void* lin_uniform_ptr(const void* p) {
     return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
 }
 
-// y[m][n] = sum_k x[m][k] * w[n][k].  Requires M % BM == 0, N % BN == 0, K % 32 == 0, every
-// row of x, w and y starting on a 16-byte boundary.  grid = (M/BM) * (N/BN) workgroups,
+// y[m][n] = sum_k x[m][k] * w[n][k].  Requires M % 256 == 0, N % BN == 0, K % 64 == 0, every
+// row of x, w and y starting on a 16-byte boundary.  grid = (M/256) * (N/BN) workgroups,
 // workgroup i on die i % 8; tiles are dealt so that one die walks all feature tiles of a row
 // band before moving on (the x band is then read from memory once per die, w stays in its L2).
-template <int BM, int BN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int BN>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
                         int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n) {
-    constexpr int MB = BM / 64, NB = BN / 64;          // 32-row / 32-feature blocks per wave
-    __shared__ __attribute__((aligned(1024))) uint16_t x_lds[kLinStages][BM * kLinBK];
-    __shared__ __attribute__((aligned(1024))) uint16_t w_lds[kLinStages][BN * kLinBK];
+    constexpr int NB = BN / 128;           // 32-feature blocks per wave
+    constexpr uint32_t kXStageBytes = kLinBM * kLinBK * 2, kWStageBytes = BN * kLinBK * 2;
+    constexpr uint32_t kXBytes = kLinStages * kXStageBytes;
+    __shared__ __attribute__((aligned(1024))) char lds[kXBytes + kLinStages * kWStageBytes];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
@@ -78,65 +82,65 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
     const int t = die * per_die + local;
     if (t >= tiles_m * tiles_n) return;
     const int tm = t / tiles_n, tn = t % tiles_n;
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+    const int64_t m0 = (int64_t)tm * kLinBM, n0 = (int64_t)tn * BN;
 
-    // ---- copies: a copy fills 16 rows of 64 bytes; lane L lands at row L/4, chunk L%4 and fetches
-    // the source chunk that the swizzle puts there (the swizzle only sees L/4: copies start on
-    // multiples of 16 rows).  Wave `wave` fills x rows (BM/4)*wave .. and w rows (BN/4)*wave .. .
-    constexpr int kXCopies = BM / 64, kWCopies = BN / 64, kCopies = kXCopies + kWCopies;   // per wave per stage
-    const int r16 = lane >> 2;
-    const int src_chunk = (lane & 3) ^ lin_swizzle(r16);
-    const uint32_t x_off = (uint32_t)(r16 * ldx * 2 + 16 * src_chunk);
-    const uint32_t w_off = (uint32_t)(r16 * ldw * 2 + 16 * src_chunk);
-    const uint32_t x_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &x_lds[0][0]);
-    const uint32_t w_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &w_lds[0][0]);
-    constexpr uint32_t kXStageBytes = BM * kLinBK * 2, kWStageBytes = BN * kLinBK * 2;
+    // ---- copies: a copy fills 8 rows of 128 bytes; lane L lands at row L/8, chunk L%8 and fetches
+    // the source chunk that the swizzle puts there.  Wave `wave` fills x rows 32*wave .. +31
+    // (4 copies) and w rows (BN/8)*wave .. (BN/64 copies); both starts are multiples of 16, so
+    // the swizzle of row 8u + L/8 of a wave's share is (4*(u & 1) + L/16) & 7.
+    constexpr int kCopies = 4 + BN / 64;   // per wave per stage
+    const int r8 = lane >> 3;
+    uint32_t x_off[2], w_off[2];           // byte offset of this lane inside an 8-row group, by parity of the group
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int chunk = (lane & 7) ^ lin_swizzle(8 * par + r8);
+        x_off[par] = (uint32_t)(r8 * ldx * 2 + 16 * chunk);
+        w_off[par] = (uint32_t)(r8 * ldw * 2 + 16 * chunk);
+    }
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &lds[0]);
 
     auto issue = [&](int ks, int stage) {
 #pragma unroll
-        for (int u = 0; u < kXCopies; ++u) {
-            const int row = (BM / 4) * wave + 16 * u;
-            lin_copy16(lin_uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off,
-                       x_lds_addr + stage * kXStageBytes + row * 64);
+        for (int u = 0; u < 4; ++u) {
+            const int row = 32 * wave + 8 * u;
+            lin_copy16(lin_uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off[u & 1],
+                       lds_addr + stage * kXStageBytes + row * 128);
         }
 #pragma unroll
-        for (int u = 0; u < kWCopies; ++u) {
-            const int row = (BN / 4) * wave + 16 * u;
-            lin_copy16(lin_uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off,
-                       w_lds_addr + stage * kWStageBytes + row * 64);
+        for (int u = 0; u < BN / 64; ++u) {
+            const int row = (BN / 8) * wave + 8 * u;
+            lin_copy16(lin_uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off[u & 1],
+                       lds_addr + kXBytes + stage * kWStageBytes + row * 128);
         }
     };
 
     // ---- fragments: lane (j, g) reads row j of a 32-row block, chunk (2*kk + g) ^ swizzle(j)
-    const int wm = wave >> 1, wn = wave & 1;
-    const int frag = j * kLinBK + 8 * (g ^ lin_swizzle(j));            // element offset for kk = 0; kk = 1 xors 16 in
-    const int x_rows = (BM / 2) * wm, w_rows = (BN / 2) * wn;          // first row of this wave in the two tiles
+    const int wm = wave >> 2, wn = wave & 3;
+    const int frag = j * kLinBK + 8 * (g ^ lin_swizzle(j));            // element offset for kk = 0; kk xors 16*kk in
+    const int x_rows = 128 * wm, w_rows = (BN / 4) * wn;               // first row of this wave in the two tiles
 
-    floatx16 acc[NB][MB];
+    floatx16 acc[NB][4];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
     const int n_k = K / kLinBK;
-#pragma unroll
-    for (int ks = 0; ks < kLinStages - 1; ++ks)
-        if (ks < n_k) issue(ks, ks);
-    int stage = 0;
+    issue(0, 0);
     for (int ks = 0; ks < n_k; ++ks) {
-        // this wave's share of stage ks has landed once only the copies of the next stage are outstanding
-        if (ks + 1 < n_k) lin_wait_vmcnt<kCopies>(); else lin_wait_vmcnt<0>();
-        __syncthreads();           // everyone's has, and everyone is done reading the stage consumed last
-        if (ks + kLinStages - 1 < n_k) issue(ks + kLinStages - 1, stage == 0 ? kLinStages - 1 : stage - 1);
-        const uint16_t* xs = x_lds[stage] + x_rows * kLinBK;
-        const uint16_t* ws = w_lds[stage] + w_rows * kLinBK;
+        const int stage = ks & 1;
+        lin_wait_vmcnt<0>();       // this wave's share of stage ks has landed
+        __syncthreads();           // everyone's has, and everyone is done reading the other stage
+        if (ks + 1 < n_k) issue(ks + 1, stage ^ 1);
+        const uint16_t* xs = reinterpret_cast<const uint16_t*>(lds + stage * kXStageBytes) + x_rows * kLinBK;
+        const uint16_t* ws = reinterpret_cast<const uint16_t*>(lds + kXBytes + stage * kWStageBytes) + w_rows * kLinBK;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 xf[MB], wf[NB];
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 xf[4], wf[NB];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < 4; ++mb)
                 xf[mb] = *reinterpret_cast<const bf16x8*>(xs + 32 * mb * kLinBK + (frag ^ (16 * kk)));
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -144,34 +148,50 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < 4; ++mb)
                     acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
         }
-        stage = stage == kLinStages - 1 ? 0 : stage + 1;
     }
 
-    // ---- epilogue: lane (j, g) holds row m0 + x_rows + 32*mb + j; registers 4*vq .. 4*vq+3 are
-    // features n0 + w_rows + 32*nb + 8*vq + 4*g .. +3
+    // ---- epilogue.  Lane (j, g) holds row x_rows + 32*mb + j of the tile; its registers
+    // 4*vq .. 4*vq+3 of block nb are features w_rows + 32*nb + 8*vq + 4*g .. +3.  Each wave
+    // transposes 64 rows at a time through its own piece of LDS: rows of BN/4 features (64 or
+    // 128 bytes) at a pitch of 16 bytes more, written 8 bytes per lane, read back 16 bytes per
+    // lane with consecutive lanes along a row, and stored as whole rows of the wave's tile.
+    __syncthreads();               // every wave is done with the stages
+    constexpr int kRowBytes = (BN / 4) * 2, kPitch = kRowBytes + 16, kLanesPerRow = kRowBytes / 16;
+    constexpr int kRowsPerStore = 64 / kLanesPerRow;
+    char* mine = lds + wave * (64 * kPitch);
+    const int srow = lane / kLanesPerRow, schunk = lane % kLanesPerRow;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        uint16_t* yrow = y + (m0 + x_rows + 32 * mb + j) * ldy + n0 + w_rows + 4 * g;
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int mbl = 0; mbl < 2; ++mbl)
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const bf16x4 o = {(__bf16)acc[nb][mb][4 * vq], (__bf16)acc[nb][mb][4 * vq + 1],
-                                  (__bf16)acc[nb][mb][4 * vq + 2], (__bf16)acc[nb][mb][4 * vq + 3]};
-                *reinterpret_cast<bf16x4*>(yrow + 32 * nb + 8 * vq) = o;
-            }
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const floatx16& a = acc[nb][2 * half + mbl];
+                    const bf16x4 o = {(__bf16)a[4 * vq], (__bf16)a[4 * vq + 1], (__bf16)a[4 * vq + 2], (__bf16)a[4 * vq + 3]};
+                    *reinterpret_cast<bf16x4*>(mine + (32 * mbl + j) * kPitch + (32 * nb + 8 * vq + 4 * g) * 2) = o;
+                }
+        // the wave reads only what it wrote itself: LDS operations of a wave complete in order
+#pragma unroll
+        for (int s = 0; s < 64 / kRowsPerStore; ++s) {
+            const int row = s * kRowsPerStore + srow;                      // row within this half
+            const u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
+            uint16_t* dst = y + (m0 + x_rows + 64 * half + row) * ldy + n0 + w_rows + 8 * schunk;
+            *reinterpret_cast<u32x4*>(dst) = v;
+        }
     }
 }
 
-template <int BM, int BN>
+template <int BN>
 hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                         int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st) {
-    const int tiles_m = (int)(M / BM), tiles_n = N / BN;
+    const int tiles_m = (int)(M / kLinBM), tiles_n = N / BN;
     const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;
-    hipLaunchKernelGGL((linear_bf16_kernel<BM, BN>), dim3(per_die * kNumXcd), dim3(256), 0, st,
+    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(per_die * kNumXcd), dim3(512), 0, st,
                        static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(y),
                        K, ldx, ldw, ldy, tiles_m, tiles_n);
     return hipGetLastError();
@@ -181,13 +201,15 @@ hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_
 
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                               int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st) {
-    // 512 workgroups run at a time (2 per CU).  The 256-row tile moves fewer bytes per flop; the
-    // 128-row tile is taken when the last round of 256-row tiles would leave too much of the chip idle.
-    const int64_t big = (M / 256) * (N / 128);
-    const int64_t rounds = (big + 511) / 512;
-    const bool small_tiles = M % 256 != 0 || big * 10 < rounds * 512 * 8;
-    return small_tiles ? launch_tiles<128, 128>(x, w, y, M, N, K, ldx, ldw, ldy, st)
-                       : launch_tiles<256, 128>(x, w, y, M, N, K, ldx, ldw, ldy, st);
+    // One workgroup per CU at a time.  The 256-feature tile moves fewer bytes per flop; the 128-feature
+    // tile is taken when the last round of wide tiles would leave too much of the chip idle.
+    bool wide = N % 256 == 0;
+    if (wide) {
+        const int64_t tiles = (M / kLinBM) * (N / 256), rounds = (tiles + 255) / 256;
+        wide = tiles * 10 >= rounds * 256 * 8;
+    }
+    return wide ? launch_tiles<256>(x, w, y, M, N, K, ldx, ldw, ldy, st)
+                : launch_tiles<128>(x, w, y, M, N, K, ldx, ldw, ldy, st);
 }
 
 }  // namespace dfa

@@ -32,9 +32,9 @@ def _linear_bar(x_exact, w_exact, y_ref):
     return 2.0 ** -8 * np.abs(y_ref) + K * 2.0 ** -24 * mag + 1e-30
 
 
-# (9216, 1536) is large enough for the 256-row tile to be chosen; the others run the 128-row tile
-@pytest.mark.parametrize("M,N,K", [(128, 128, 32), (256, 128, 64), (512, 256, 96), (640, 384, 160), (1024, 2304, 768),
-                                   (512, 768, 768), (9216, 1536, 96)])
+# (36864, 1024) is large enough for the 256-feature tile to be chosen; the others run the 128-feature tile
+@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (512, 256, 128), (768, 384, 192), (1024, 2304, 768), (512, 768, 768),
+                                   (36864, 1024, 128)])
 def test_linear_against_fp64_matmul(B, oracle, M, N, K):
     x, xe = _bf16(401, 3, (M, K))
     w, we = _bf16(401, 10, (N, K), std=0.02)
@@ -69,10 +69,10 @@ def test_linear_rejects_bad_shapes(B):
     x = torch.zeros((256, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.zeros((128, 64), dtype=torch.bfloat16, device="cuda")
     B.linear(x, w)
-    for bad_x, bad_w in ((torch.zeros((192, 64), dtype=torch.bfloat16, device="cuda"), w),
+    for bad_x, bad_w in ((torch.zeros((384, 64), dtype=torch.bfloat16, device="cuda"), w),
                          (x, torch.zeros((100, 64), dtype=torch.bfloat16, device="cuda")),
-                         (torch.zeros((256, 48), dtype=torch.bfloat16, device="cuda"),
-                          torch.zeros((128, 48), dtype=torch.bfloat16, device="cuda"))):
+                         (torch.zeros((256, 96), dtype=torch.bfloat16, device="cuda"),
+                          torch.zeros((128, 96), dtype=torch.bfloat16, device="cuda"))):
         with pytest.raises(B.DfaError) as e:
             B.linear(bad_x, bad_w)
         assert e.value.code == -2
