@@ -87,6 +87,87 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
             "note": "unfused_path_ms = the three unmerged branch launches + merge; the fused dfa_forward does all of it in one launch"}
 
 
+def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline):
+    """The encoder attention stack: 12 layers, embed 768 = 12 heads x 64, B = 8 images of 4096 tokens, bf16;
+    per layer QKV projection (768 -> 2304), dilated attention, output projection (768 -> 768); weights
+    N(0, 0.02^2), input N(0, 1), no bias, residual or normalisation.  One step = all 12 layers."""
+    cfg = synth.CONFIGS["stack_layer"]
+    Bsz, H, N, D, branches = cfg["B"], cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
+    E, layers, scale, seed = H * D, 12, 1.0 / (D ** 0.5), cfg["seed"]
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    xb, xe = synth.tensor(seed, synth.TENSOR_X, (Bsz, N, E), "bf16")
+    wq_bits, wo_bits = [], []
+    for l in range(layers):
+        wq_bits.append(synth.tensor(seed, 10 + 2 * l, (3 * E, E), "bf16", std=0.02)[0])
+        wo_bits.append(synth.tensor(seed, 11 + 2 * l, (E, E), "bf16", std=0.02)[0])
+    x, wq, wo = dev(xb), dev(np.stack(wq_bits)), dev(np.stack(wo_bits))
+    ws = (torch.empty((Bsz, N, 3, H, D), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((Bsz, N, H, D), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((Bsz, N, E), dtype=torch.bfloat16, device="cuda"))
+
+    def run():
+        return binding.encoder_stack(x, wq, wo, H, branches, scale, workspace=ws)
+
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    M = Bsz * N
+    fl_attn = synth.useful_flops(Bsz, H, N, D, branches)
+    fl_qkv, fl_out = 2 * M * 3 * E * E, 2 * M * E * E
+    flops = layers * (fl_attn + fl_qkv + fl_out)
+
+    def timed(fn, it=50):
+        for _ in range(5):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(it):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / it
+
+    qkv, attn, y = ws
+    ms_qkv = timed(lambda: binding.linear(x, wq[0], out=qkv.view(Bsz, N, 3 * E)))
+    ms_attn = timed(lambda: binding.forward(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], branches, scale, out=attn, want_lse=False))
+    ms_out = timed(lambda: binding.linear(attn.view(Bsz, N, E), wo[0], out=y))
+
+    cpu = None
+    if cpu_baseline:
+        # one layer of one image: (b, h) units and images are independent, so the per-image time is exact
+        from oracle import dfa_oracle
+        wqe = synth.bf16_bits_to_f64(wq_bits[0])
+        woe = synth.bf16_bits_to_f64(wo_bits[0])
+        t0 = time.perf_counter()
+        dfa_oracle.attention_layer(xe[:1], wqe, woe, H, branches, scale)
+        dt = time.perf_counter() - t0
+        cpu = {"value": dt * layers * 1e6, "unit": "us per image (all layers)", "cores": dfa_oracle.num_threads(),
+               "kind": "oracle", "seconds": round(dt, 3),
+               "sample": "one layer of one image in fp64 (numpy matmul projections + the C attention oracle), times 12 layers"}
+    return {
+        "metric": "us per 1024x1024 image, all 12 layers of the encoder attention stack", "value": wall * 1e6 / Bsz,
+        "unit": "us/image", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall * 1e3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"stack: 12 layers, embed {E}, H={H} D={D}, B={Bsz}, N={N}, branches={branches}, "
+                               "QKV projection + dilated attention + output projection per layer"},
+        "useful_tflops": flops / wall / 1e12, "pct_of_mfma_peak": 100.0 * flops / wall / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "per_layer_kernels": {
+            "qkv_projection": {"ms": ms_qkv, "TFLOP/s": fl_qkv / ms_qkv / 1e9},
+            "dilated_attention": {"ms": ms_attn, "TFLOP/s": fl_attn / ms_attn / 1e9},
+            "output_projection": {"ms": ms_out, "TFLOP/s": fl_out / ms_out / 1e9}},
+        "cpu_baseline": cpu,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +178,9 @@ def main():
     ap.add_argument("--stages", action="store_true",
                     help="time the stand-alone stage kernels (gather, placement, unmerged branches, merge) "
                          "on the same workload and print their achieved HBM GB/s instead of the default line")
+    ap.add_argument("--stack", action="store_true",
+                    help="time the encoder attention stack workload (12 layers of QKV projection + dilated attention "
+                         "+ output projection at B = 8) and print its line instead of the default one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
@@ -124,6 +208,10 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_each_way": n, "copies": 5}))
+        return
+
+    if args.stack:
+        print(json.dumps(stack_report(binding, synth, torch, np, args.steps, args.warmup, not args.no_cpu_baseline)))
         return
 
     cfg = synth.CONFIGS[args.workload]
