@@ -534,23 +534,61 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
     // ---- epilogue: normalise, log-sum-exp, place each row at its own token (Eq. 3)
     const int j_e = lane_e & 31, g_e = lane_e >> 5;
+    float inv[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int slot = wave * 64 + qb * 32 + j_e;
         const float l_tot = wave_half_sum(l_run[qb]);
-        const float inv = 1.0f / l_tot;
-        if (slot < tile.nrows) {
-            const int64_t n = row_idx[slot];
-            OutT* op = out + (out_bh + n * p.H) * kD;
+        inv[qb] = 1.0f / l_tot;
+        if (p.lse && g_e == 0 && slot < tile.nrows)
+            p.lse[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
+    if constexpr (sizeof(OutT) == 2) {
+        // bf16 rows are 128 bytes.  A lane holds 4 consecutive d of one row per register quad; written
+        // out directly that would be 8-byte pieces of 32 different lines per store.  Each wave
+        // instead lays its 64 rows out row-major in a piece of the (now idle) K / V stages, at a
+        // pitch of 144 bytes, and stores them 16 bytes per lane, eight lanes to a row: whole lines.
+        __syncthreads();           // every wave is done with the stages
+        constexpr int kPitch = kD * 2 + 16;
+        char* mine = reinterpret_cast<char*>(wave < 2 ? &k_lds[0][0] : &v_lds[0][0]) + (wave & 1) * (64 * kPitch);
+        if (wave_live) {
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int vq = 0; vq < 4; ++vq)
-                    store4<OutT>(op + 32 * db + 8 * vq + 4 * g_e,
-                                 oacc[db][qb][4 * vq] * inv, oacc[db][qb][4 * vq + 1] * inv,
-                                 oacc[db][qb][4 * vq + 2] * inv, oacc[db][qb][4 * vq + 3] * inv);
-            if (p.lse && g_e == 0)
-                p.lse[((int64_t)b * p.H + h) * p.N + n] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const bf16x4 o = {(__bf16)(oacc[db][qb][4 * vq] * inv[qb]), (__bf16)(oacc[db][qb][4 * vq + 1] * inv[qb]),
+                                          (__bf16)(oacc[db][qb][4 * vq + 2] * inv[qb]), (__bf16)(oacc[db][qb][4 * vq + 3] * inv[qb])};
+                        *reinterpret_cast<bf16x4*>(mine + (32 * qb + j_e) * kPitch + (32 * db + 8 * vq + 4 * g_e) * 2) = o;
+                    }
+            // the wave reads back only what it wrote itself; LDS operations of a wave complete in order
+            const int srow = lane_e >> 3, schunk = lane_e & 7;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int row = 8 * s + srow, slot = wave * 64 + row;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
+                if (slot < tile.nrows) {
+                    const int64_t n = row_idx[slot];
+                    *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(out + (out_bh + n * p.H) * kD) + 16 * schunk) = val;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int slot = wave * 64 + qb * 32 + j_e;
+            if (slot < tile.nrows) {
+                const int64_t n = row_idx[slot];
+                OutT* op = out + (out_bh + n * p.H) * kD;
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq)
+                        store4<OutT>(op + 32 * db + 8 * vq + 4 * g_e,
+                                     oacc[db][qb][4 * vq] * inv[qb], oacc[db][qb][4 * vq + 1] * inv[qb],
+                                     oacc[db][qb][4 * vq + 2] * inv[qb], oacc[db][qb][4 * vq + 3] * inv[qb]);
+            }
         }
     }
 }
