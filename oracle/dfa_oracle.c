@@ -17,6 +17,13 @@
  *   3. Recomposition (Eq. 3 and its steps (1)-(3)): a zero matrix of the input's
  *      shape receives every segment's rows at the token positions they were
  *      taken from; rows that no segment keeps stay zero (their lse is -inf).
+ *      The paper cuts the sequence into "equal-length parts"; where w does not
+ *      divide N the attention functions take the last part shorter (the same as
+ *      padding the sequence to a multiple of w and giving padded keys weight
+ *      zero), w > N gives one part, and where r does not divide w a part keeps
+ *      its rows o, o + r, o + 2r, ... below its end.  Token n is in part
+ *      floor(n / w) and is kept iff n - floor(n / w) * w - o is a non-negative
+ *      multiple of r.  The index map keeps the regular case only (w | N, r | w).
  *   4. Branch merge (workload definition; the paper treats one (w, r) only):
  *      L = log sum_b exp(lse_b), out = sum_b exp(lse_b - L) * out_b over the
  *      branches that keep the row.
@@ -41,6 +48,21 @@
 
 static int branch_ok(int N, int w, int r) {
     return N > 0 && w > 0 && r > 0 && w <= N && (N % w) == 0 && (w % r) == 0;
+}
+
+/* The attention functions also take ragged partitions (see the header). */
+static int branch_general_ok(int N, int w, int r) {
+    return N > 0 && w > 0 && r > 0;
+}
+
+/* Kept rows of part i of a branch, ascending, into rows[]; returns how many. */
+static int kept_rows_of_part(int N, int w, int r, int o, int i, int *rows) {
+    const long long first = (long long)i * w + o;
+    long long end = (long long)(i + 1) * w;
+    if (end > N) end = N;
+    int n_keep = 0;
+    for (long long n = first; n < end; n += r) rows[n_keep++] = (int)n;
+    return n_keep;
 }
 
 static int head_offset(const int *head_offsets, int h, int r) {
@@ -116,13 +138,14 @@ int dfa_oracle_branch(const double *q, const double *k, const double *v,
                       int B, int H, int N, int D, double scale,
                       int w, int r, const int *head_offsets,
                       double *out_b, double *lse_b) {
-    if (!q || !k || !v || !out_b || !lse_b || B <= 0 || H <= 0 || D <= 0 || !branch_ok(N, w, r)) return -1;
+    if (!q || !k || !v || !out_b || !lse_b || B <= 0 || H <= 0 || D <= 0 || !branch_general_ok(N, w, r)) return -1;
     for (int h = 0; h < H; ++h) {
         const int o = head_offset(head_offsets, h, r);
         if (o < 0 || o >= r) return -1;
     }
     const size_t tok = (size_t)H * D;
-    const int per_seg = w / r;
+    const int per_seg = (w < N ? w : N) / r + 1;                   /* room for the kept rows of one part */
+    const int n_parts = (N + w - 1) / w;
     memset(out_b, 0, sizeof(double) * (size_t)B * N * H * D);      /* O_init = 0 */
     for (size_t x = 0; x < (size_t)B * H * N; ++x) lse_b[x] = -INFINITY;
     int failed = 0;
@@ -136,9 +159,9 @@ int dfa_oracle_branch(const double *q, const double *k, const double *v,
             } else {
                 const int o = head_offset(head_offsets, h, r);
                 const size_t base = (size_t)b * N * tok + (size_t)h * D;
-                for (int i = 0; i < N / w; ++i) {
-                    for (int j = 0; j < per_seg; ++j) rows[j] = i * w + o + j * r;
-                    segment_attention(q + base, k + base, v + base, tok, D, scale, rows, per_seg,
+                for (int i = 0; i < n_parts; ++i) {
+                    const int n_keep = kept_rows_of_part(N, w, r, o, i, rows);
+                    segment_attention(q + base, k + base, v + base, tok, D, scale, rows, n_keep,
                                       out_b + base, lse_b + ((size_t)b * H + h) * N, t, NULL);
                 }
             }
@@ -257,7 +280,7 @@ int dfa_oracle_forward_rows(const double *q, const double *k, const double *v,
                             int nb, const int *w, const int *r, const int *head_offsets,
                             int n_rows, const int *bhn, double *out_rows, double *lse_rows) {
     if (!q || !k || !v || nb <= 0 || !w || !r || !bhn || !out_rows || !lse_rows || D <= 0) return -1;
-    for (int x = 0; x < nb; ++x) if (!branch_ok(N, w[x], r[x])) return -1;
+    for (int x = 0; x < nb; ++x) if (!branch_general_ok(N, w[x], r[x])) return -1;
     const size_t tok = (size_t)H * D;
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -278,7 +301,9 @@ int dfa_oracle_forward_rows(const double *q, const double *k, const double *v,
                 lb[x] = -INFINITY;
                 for (int d = 0; d < D; ++d) ob[x * D + d] = 0.0;
                 if (pos < 0 || pos % r[x] != 0) continue;           /* row not kept by this branch */
-                const int per_seg = w[x] / r[x];
+                long long part_end = (long long)(seg + 1) * w[x];
+                if (part_end > N) part_end = N;
+                const int per_seg = (int)((part_end - 1 - ((long long)seg * w[x] + o)) / r[x]) + 1;
                 double m = -INFINITY;
                 for (int j = 0; j < per_seg; ++j) {
                     const double *kc = k + base + (size_t)(seg * w[x] + o + j * r[x]) * tok;

@@ -17,7 +17,8 @@ def multiplicity_matrix(N, h, branches, head_offsets=None):
     mult = np.zeros((N, N), dtype=np.int64)
     for x, (w, r) in enumerate(branches):
         o = (h % r) if head_offsets is None else int(head_offsets[x][h])
-        kept = (n % r) == o
+        pos = n - (n // w) * w - o                  # position inside the part, counted from the head's start
+        kept = (pos >= 0) & (pos % r == 0)
         same_seg = (n[:, None] // w) == (n[None, :] // w)
         mult += (same_seg & kept[:, None] & kept[None, :]).astype(np.int64)
     return mult

@@ -355,3 +355,46 @@ def test_attention_layer_reduces_to_the_operator_with_identity_projections(oracl
     vh = xh * np.array([5.0, 35.0])[None, None, :, None]
     ref2, _ = oracle.forward(2 * xh, 3 * xh, vh, branches, 0.5)
     assert np.abs(y2 - ref2.reshape(B, N, E)[..., ::-1]).max() < 1e-12
+
+
+# ---------------------------------------------------------------- ragged partitions (w does not divide N, w > N, r does not divide w)
+@pytest.mark.parametrize("N,branches,offs", [
+    (50, [(16, 3)], None),                       # last part has 2 tokens; 16 % 3 != 0
+    (50, [(7, 2), (64, 5)], None),               # w > N: one part; 7 % 2 != 0
+    (45, [(10, 1), (20, 4), (45, 9)], [[0, 0, 0], [3, 1, 0], [8, 2, 5]]),
+    (33, [(32, 1)], None),                       # a last part of a single token
+])
+def test_ragged_partitions_match_the_brute_force(oracle, N, branches, offs):
+    """Token n is in part floor(n / w) and kept iff n - floor(n / w) * w - o is a non-negative multiple
+    of r: the oracle's loops over parts against the multiplicity-weighted softmax written from that
+    sentence alone."""
+    rng = np.random.default_rng(21)
+    B, H, D = 2, 3, 4
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    out, lse = oracle.forward(q, k, v, branches, 0.7, head_offsets=offs)
+    o_ref, l_ref = multiset_attention(q, k, v, 0.7, branches, head_offsets=offs)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(l_ref))
+    fin = ~np.isneginf(l_ref)
+    assert np.abs(out - o_ref).max() < 1e-12 and np.abs(lse[fin] - l_ref[fin]).max() < 1e-12
+    bhn = np.array([[b, h, n] for b in range(B) for h in range(H) for n in range(N)], dtype=np.int32)
+    o_rows, l_rows = oracle.forward_rows(q, k, v, branches, 0.7, bhn, head_offsets=offs)
+    assert np.abs(o_rows - out[bhn[:, 0], bhn[:, 2], bhn[:, 1]]).max() < 1e-12
+    got_l, want_l = l_rows, lse[bhn[:, 0], bhn[:, 1], bhn[:, 2]]
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(want_l))
+    assert np.abs(got_l[~np.isneginf(want_l)] - want_l[~np.isneginf(want_l)]).max() < 1e-12
+
+
+def test_short_last_part_is_dense_attention_on_its_slice(oracle):
+    """r = 1: every part, the short last one included, is plain softmax attention over its own
+    tokens; w > N is plain attention over the whole sequence."""
+    rng = np.random.default_rng(22)
+    N, D, w = 23, 5, 8
+    q, k, v = (rng.standard_normal((1, N, 1, D)) for _ in range(3))
+    out, lse = oracle.forward(q, k, v, [(w, 1)], 0.9)
+    for lo in range(0, N, w):
+        hi = min(N, lo + w)
+        o_ref, l_ref = dense_softmax_attention(q[0, lo:hi, 0], k[0, lo:hi, 0], v[0, lo:hi, 0], 0.9)
+        assert np.abs(out[0, lo:hi, 0] - o_ref).max() < 1e-13 and np.abs(lse[0, 0, lo:hi] - l_ref).max() < 1e-13
+    out2, lse2 = oracle.forward(q, k, v, [(40, 1)], 0.9)
+    o_ref, l_ref = dense_softmax_attention(q[0, :, 0], k[0, :, 0], v[0, :, 0], 0.9)
+    assert np.abs(out2[0, :, 0] - o_ref).max() < 1e-13 and np.abs(lse2[0, 0] - l_ref).max() < 1e-13
