@@ -11,6 +11,12 @@
  *     1/sqrt(D) for the usual flash-attention convention.
  *   - Recomposition (Eq. 3): results are placed at the token positions they were taken
  *     from in a zero matrix of the input's shape; rows that nothing keeps are 0.
+ *   - The paper cuts the sequence into equal-length parts.  The attention entry points also
+ *     take other shapes: token n lies in part floor(n / w) and is kept iff
+ *     n - floor(n / w) * w - o is a non-negative multiple of r, so the last part is shorter
+ *     when w does not divide N (the same as padding the sequence and giving padded keys no
+ *     weight), w > N gives a single part, and r need not divide w.  The index map, gather and
+ *     placement entry points keep the regular case (w <= N, N % w == 0, w % r == 0).
  *   - Several (w, r) branches are merged with their log-sum-exp weights:
  *     L = log sum_b exp(lse_b), out = sum_b exp(lse_b - L) * out_b over the branches that
  *     keep the row (the paper treats a single branch; nb = 1 reproduces it).
@@ -48,8 +54,10 @@ extern "C" {
 typedef enum {
     DFA_OK = 0,
     DFA_ERR_NULL = -1,      /* a required pointer is NULL                                    */
-    DFA_ERR_SHAPE = -2,     /* B, H, N <= 0; D != 64; w > N; N % w != 0; w % r != 0; r < 1;  */
-                            /* head offset outside [0, r); scale not finite or <= 0          */
+    DFA_ERR_SHAPE = -2,     /* B, H, N <= 0; D != 64; w < 1; r < 1; head offset outside      */
+                            /* [0, r); scale not finite or <= 0; for the index map, gather   */
+                            /* and placement also w > N, N % w != 0, w % r != 0; for the     */
+                            /* projections sizes that the tiles do not divide                */
     DFA_ERR_BRANCHES = -3,  /* nb < 1 or nb > DFA_MAX_BRANCHES                               */
     DFA_ERR_DTYPE = -4,     /* unknown dfa_dtype_t                                           */
     DFA_ERR_ALIGN = -5,     /* a base pointer or stride breaks the 16-byte row alignment     */

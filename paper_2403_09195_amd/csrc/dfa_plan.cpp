@@ -12,7 +12,7 @@ int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, con
     if (H <= 0 || N <= 0) return DFA_ERR_SHAPE;
     for (int x = 0; x < nb; ++x) {
         const int32_t w = br[x].w, r = br[x].r;
-        if (r < 1 || w < r || w > N || N % w != 0 || w % r != 0) return DFA_ERR_SHAPE;
+        if (r < 1 || w < 1) return DFA_ERR_SHAPE;
         if (offsets)
             for (int h = 0; h < H; ++h) {
                 const int32_t o = offsets[(int64_t)x * H + h];
@@ -37,7 +37,8 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
         for (int32_t n = 0; n < N; ++n) {
             for (int x = 0; x < nb; ++x) {
                 const int32_t o = head_offset(offsets, H, x, h, br[x].r);
-                sig[x] = (n % br[x].r == o) ? n / br[x].w : -1;
+                const int32_t part = n / br[x].w, pos = n - part * br[x].w - o;   // position inside the part
+                sig[x] = (pos >= 0 && pos % br[x].r == 0) ? part : -1;
             }
             groups[sig].push_back(n);
         }
@@ -50,8 +51,13 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             for (int x = 0; x < nb; ++x) {
                 if (s[x] < 0) continue;
                 const int32_t o = head_offset(offsets, H, x, h, br[x].r);
-                plan->segs.push_back(KeySeg{s[x] * br[x].w + o, br[x].r, br[x].w / br[x].r, 0});
-                keys += br[x].w / br[x].r;
+                // kept keys of the part: first, first + r, ... below the end of the part (the last part
+                // is shorter when w does not divide N)
+                const int64_t first = (int64_t)s[x] * br[x].w + o;
+                const int64_t end = std::min<int64_t>((int64_t)(s[x] + 1) * br[x].w, N);
+                const int32_t count = (int32_t)((end - 1 - first) / br[x].r + 1);   // >= 1: a row of the part is kept
+                plan->segs.push_back(KeySeg{(int32_t)first, br[x].r, count, 0});
+                keys += count;
                 ++nseg;
             }
             for (size_t lo = 0; lo < rows.size(); lo += kTileRows) {

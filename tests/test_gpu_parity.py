@@ -175,6 +175,27 @@ def test_bf16_key_counts_around_the_pipeline_beats(B, oracle, count, r):
     _check_bf16(out1, lse1, o1, l1, f"bf16 count {count} r {r}, one branch")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,branches,offs", [
+    (1000, [(300, 1), (128, 3), (2048, 7)], None),                 # w does not divide N, r does not divide w, w > N
+    (1025, [(1024, 1), (512, 2)], None),                           # a last part of a single token
+    (777, [(100, 4), (250, 5), (777, 9)], [[3, 0], [4, 2], [8, 1]]),
+])
+def test_ragged_partitions(B, oracle, dtype, N, branches, offs):
+    """Shapes the paper's equal-length parts do not cover: short last part, one part for w > N,
+    every r-th row of a part from the head's start when r does not divide w."""
+    H = 2
+    (q, k, v), ex = make_qkv(320 + N, 2, N, H, 64, dtype)
+    out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
+    if dtype == "bf16":
+        _check_bf16(out, lse, o_ref, l_ref, f"ragged N={N}")
+    else:
+        _check_f32(out, lse, o_ref, l_ref, f"ragged N={N}")
+    dead = np.isneginf(l_ref).transpose(0, 2, 1)
+    assert np.all(to_f64(out)[dead] == 0.0)
+
+
 def test_bf16_reference_exponent_moves_when_logits_keep_growing(B, oracle):
     """Keys ordered so that logits grow along every key list (and jump between lists): the
     reference exponent of the online softmax has to move many times, also late in the walk,
