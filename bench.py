@@ -87,13 +87,40 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
             "note": "unfused_path_ms = the three unmerged branch launches + merge; the fused dfa_forward does all of it in one launch"}
 
 
-def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline):
+def sweep_report(binding, synth, torch, np, steps, warmup):
+    """Section 4.4's ablation as a synthetic sweep: image sizes 256^2, 512^2, 1024^2 (N = 256, 1024, 4096
+    tokens of 16 x 16 patches), embed 384 (6 heads) and 768 (12 heads), B = 16.  For each shape the three
+    dilated branches scaled to it ((N/4, 1), (N/2, 2), (N, 4)) against dense attention over all N tokens,
+    both through dfa_forward (dense = one branch with w = N, r = 1)."""
+    rows = []
+    Bsz, D, scale = 16, 64, 0.125
+    for H in (6, 12):
+        for N in (256, 1024, 4096):
+            st, _ = synth.qkv(synth.BASE_SEED + 10 + H + N, Bsz, N, H, D, "bf16")
+            q, k, v = (torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda() for a in st)
+            out = torch.empty_like(q)
+            lse = torch.empty((Bsz, H, N), dtype=torch.float32, device="cuda")
+            dil = [(N // 4, 1), (N // 2, 2), (N, 4)]
+            res = {"image": f"{int(N ** 0.5) * 16}^2", "N": N, "H": H, "B": Bsz}
+            for name, br in (("dilated", dil), ("dense", [(N, 1)])):
+                for _ in range(max(warmup, 3)):
+                    binding.forward(q, k, v, br, scale, out=out, lse=lse)
+                ms = binding.forward_timed(q, k, v, br, scale, max(steps // 4, 10), out=out, lse=lse)
+                fl = synth.useful_flops(Bsz, H, N, D, br)
+                res[name] = {"us": ms * 1e3, "useful_TFLOP/s": fl / ms / 1e9, "flops": fl}
+            res["dense_over_dilated_time"] = res["dense"]["us"] / res["dilated"]["us"]
+            rows.append(res)
+    return {"sweep": rows, "note": "useful FLOPs = 4*D per (query, key) pair the method computes; dense attention "
+                                    "computes N^2 pairs per head, the three branches 7*N^2/16"}
+
+
+def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=12, H=12):
     """The encoder attention stack: 12 layers, embed 768 = 12 heads x 64, B = 8 images of 4096 tokens, bf16;
     per layer QKV projection (768 -> 2304), dilated attention, output projection (768 -> 768); weights
     N(0, 0.02^2), input N(0, 1), no bias, residual or normalisation.  One step = all 12 layers."""
     cfg = synth.CONFIGS["stack_layer"]
-    Bsz, H, N, D, branches = cfg["B"], cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
-    E, layers, scale, seed = H * D, 12, 1.0 / (D ** 0.5), cfg["seed"]
+    Bsz, N, D, branches = cfg["B"], cfg["N"], cfg["D"], cfg["branches"]
+    E, scale, seed = H * D, 1.0 / (D ** 0.5), cfg["seed"]
 
     def dev(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
@@ -152,12 +179,12 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline):
         dt = time.perf_counter() - t0
         cpu = {"value": dt * layers * 1e6, "unit": "us per image (all layers)", "cores": dfa_oracle.num_threads(),
                "kind": "oracle", "seconds": round(dt, 3),
-               "sample": "one layer of one image in fp64 (numpy matmul projections + the C attention oracle), times 12 layers"}
+               "sample": f"one layer of one image in fp64 (numpy matmul projections + the C attention oracle), times {layers} layers"}
     return {
-        "metric": "us per 1024x1024 image, all 12 layers of the encoder attention stack", "value": wall * 1e6 / Bsz,
+        "metric": f"us per 1024x1024 image, all {layers} layers of the encoder attention stack", "value": wall * 1e6 / Bsz,
         "unit": "us/image", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"stack: 12 layers, embed {E}, H={H} D={D}, B={Bsz}, N={N}, branches={branches}, "
+        "config": {"workload": f"stack: {layers} layers, embed {E}, H={H} D={D}, B={Bsz}, N={N}, branches={branches}, "
                                "QKV projection + dilated attention + output projection per layer"},
         "useful_tflops": flops / wall / 1e12, "pct_of_mfma_peak": 100.0 * flops / wall / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "per_layer_kernels": {
@@ -181,6 +208,11 @@ def main():
     ap.add_argument("--stack", action="store_true",
                     help="time the encoder attention stack workload (12 layers of QKV projection + dilated attention "
                          "+ output projection at B = 8) and print its line instead of the default one")
+    ap.add_argument("--sweep", action="store_true",
+                    help="input-size sweep of the paper's ablation (256^2, 512^2, 1024^2 images; 6 and 12 heads): "
+                         "dilated attention against dense attention in the same kernel (w = N, r = 1)")
+    ap.add_argument("--layers", type=int, default=12, help="--stack: number of layers")
+    ap.add_argument("--heads", type=int, default=12, help="--stack: heads of 64 (embed = 64 * heads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
@@ -211,7 +243,11 @@ def main():
         return
 
     if args.stack:
-        print(json.dumps(stack_report(binding, synth, torch, np, args.steps, args.warmup, not args.no_cpu_baseline)))
+        print(json.dumps(stack_report(binding, synth, torch, np, args.steps, args.warmup, not args.no_cpu_baseline,
+                                      args.layers, args.heads)))
+        return
+    if args.sweep:
+        print(json.dumps(sweep_report(binding, synth, torch, np, args.steps, args.warmup)))
         return
 
     cfg = synth.CONFIGS[args.workload]
