@@ -284,6 +284,10 @@ def main():
     kern_ms = binding.forward_timed(q, k, v, branches, scale, args.steps, out=out, lse=lse)
     achieved = flops / (kern_ms * 1e-3) / 1e12
 
+    # the matrix cores on their own, measured now on this machine: constant and random operands
+    peak_const, mhz_const = binding.mfma_peak(False)
+    peak_rand, mhz_rand = binding.mfma_peak(True)
+
     # sampled parity against the oracle (cheap sanity check of what was just timed)
     from oracle import dfa_oracle
     rng = np.random.default_rng(1)
@@ -311,6 +315,9 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={Bsz} H={H} N={N} D={D} branches={branches} offset=h mod r scale=1/sqrt(D)"},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+        "mfma_only_loop": {"constant_operands": {"TFLOP/s": peak_const, "shader_MHz": mhz_const},
+                           "random_operands": {"TFLOP/s": peak_rand, "shader_MHz": mhz_rand},
+                           "pct_of_random_operand_ceiling": 100.0 * tflops / peak_rand},
         "us_per_image_per_layer": ms_per_step * 1e3 / Bsz,
         "us_per_image_12_layers_attention_only": 12 * ms_per_step * 1e3 / Bsz,
         "useful_flops_per_step": flops,

@@ -211,6 +211,19 @@ int dfa_forward_timed(const void *q, const void *k, const void *v,
                       const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
                       void *out, float *lse, void *stream, int32_t iters, float *ms);
 
+/*
+ * Measurement aid (no part of the operator): what the matrix cores sustain on their own, the
+ * ceiling that the kernels' MFMA rooflines are also quoted against.  Runs a loop of
+ * independent v_mfma_f32_32x32x16_bf16 on the whole chip (two waves per SIMD, no memory
+ * traffic) on the default stream and synchronises.
+ *   random_operands  0: small constant operands; 1: pseudo-random bf16 operands (more bits
+ *                    toggle, the sustained clock is lower)
+ *   tflops           out, host: achieved TFLOP/s
+ *   shader_mhz       out, host: shader clock during the loop (cycle counter / 100 MHz wall counter)
+ * Allocates and frees a few bytes of device memory.
+ */
+int dfa_mfma_peak(int32_t random_operands, float *tflops, float *shader_mhz);
+
 #ifdef __cplusplus
 }
 #endif

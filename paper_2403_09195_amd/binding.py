@@ -18,7 +18,7 @@ DFA_MAX_BRANCHES = 8
 EXPORTS = [
     "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_forward",
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
-    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack",
+    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack", "dfa_mfma_peak",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
         L.dfa_linear.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
         L.dfa_encoder_stack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, ctypes.POINTER(Branch), i32,
                                         _i32p, vp, vp, vp, vp]
+        L.dfa_mfma_peak.argtypes = [i32, ctypes.POINTER(f32), ctypes.POINTER(f32)]
         for name in EXPORTS:
             if name != "dfa_error_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -302,6 +303,13 @@ def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, workspac
                                    vp(qkv.data_ptr()), vp(attn.data_ptr()), vp(y.data_ptr()), _stream()),
            "dfa_encoder_stack")
     return y, qkv, attn
+
+
+def mfma_peak(random_operands=True):
+    """(TFLOP/s, shader MHz) of an MFMA-only loop on the whole chip; synchronises."""
+    t, m = ctypes.c_float(0.0), ctypes.c_float(0.0)
+    _check(lib().dfa_mfma_peak(1 if random_operands else 0, ctypes.byref(t), ctypes.byref(m)), "dfa_mfma_peak")
+    return t.value, m.value
 
 
 def plan_describe(B, H, N, branches, head_offsets=None):
