@@ -327,3 +327,74 @@ int dfa_oracle_forward_rows(const double *q, const double *k, const double *v,
     }
     return failed ? -1 : 0;
 }
+
+
+/*
+ * Gradients of the operator with respect to q, k and v for a given gradient dout of its
+ * output (lse takes no gradient).  The paper states no backward pass (it distils through
+ * the FlashAttention library, section 4.4); this is the chain rule applied to Eq. 2 and the
+ * branch merge.  The merged operator is a softmax over the multiset union of a row's key
+ * sets:  out_n = sum over branches x and keys j of part_x(n) of P_x(n,j) v_j  with
+ * P_x(n,j) = exp(scale q_n.k_j - lse_n), lse_n the merged log-sum-exp.  With
+ * delta_n = dout_n . out_n:
+ *   dv_j += P dout_n
+ *   ds    = P (dout_n . v_j - delta_n)
+ *   dq_n += scale ds k_j,   dk_j += scale ds q_n
+ * summed over every (branch, n, j) pair of the definition.  Plain loops, fp64; one (b, h) per
+ * thread.  dq, dk, dv are [B,N,H,D] like q.
+ */
+int dfa_oracle_backward(const double *q, const double *k, const double *v, const double *dout,
+                        int B, int H, int N, int D, double scale,
+                        int nb, const int *w, const int *r, const int *head_offsets,
+                        double *dq, double *dk, double *dv) {
+    if (!q || !k || !v || !dout || !dq || !dk || !dv || nb <= 0 || !w || !r || B <= 0 || H <= 0 || D <= 0) return -1;
+    for (int x = 0; x < nb; ++x) if (!branch_general_ok(N, w[x], r[x])) return -1;
+    const size_t total = (size_t)B * N * H * D, rows_total = (size_t)B * N * H;
+    double *out = (double *)malloc(sizeof(double) * total);
+    double *lse = (double *)malloc(sizeof(double) * rows_total);
+    if (!out || !lse) { free(out); free(lse); return -1; }
+    int rc = dfa_oracle_forward(q, k, v, B, H, N, D, scale, nb, w, r, head_offsets, out, lse, NULL, NULL);
+    if (rc != 0) { free(out); free(lse); return rc; }
+    memset(dq, 0, sizeof(double) * total);
+    memset(dk, 0, sizeof(double) * total);
+    memset(dv, 0, sizeof(double) * total);
+    const size_t tok = (size_t)H * D;
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            int *rows = (int *)malloc(sizeof(int) * (N + 1));
+            if (!rows) { failed = 1; continue; }
+            const size_t base = (size_t)b * N * tok + (size_t)h * D;
+            const double *L = lse + ((size_t)b * H + h) * N;
+            for (int x = 0; x < nb; ++x) {
+                const int o = head_offset(head_offsets ? head_offsets + (size_t)x * H : NULL, h, r[x]);
+                const int n_parts = (N + w[x] - 1) / w[x];
+                for (int i = 0; i < n_parts; ++i) {
+                    const int n_keep = kept_rows_of_part(N, w[x], r[x], o, i, rows);
+                    for (int a = 0; a < n_keep; ++a) {
+                        const size_t rn = base + (size_t)rows[a] * tok;
+                        double delta = 0.0;
+                        for (int d = 0; d < D; ++d) delta += dout[rn + d] * out[rn + d];
+                        for (int c = 0; c < n_keep; ++c) {
+                            const size_t rj = base + (size_t)rows[c] * tok;
+                            double t = 0.0, dp = 0.0;
+                            for (int d = 0; d < D; ++d) { t += q[rn + d] * k[rj + d]; dp += dout[rn + d] * v[rj + d]; }
+                            const double P = exp(scale * t - L[rows[a]]);
+                            const double ds = P * (dp - delta);
+                            for (int d = 0; d < D; ++d) {
+                                dv[rj + d] += P * dout[rn + d];
+                                dq[rn + d] += scale * ds * k[rj + d];
+                                dk[rj + d] += scale * ds * q[rn + d];
+                            }
+                        }
+                    }
+                }
+            }
+            free(rows);
+        }
+    }
+    free(out);
+    free(lse);
+    return failed ? -1 : 0;
+}

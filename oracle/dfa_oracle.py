@@ -38,7 +38,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         for name in ("dfa_oracle_index_map", "dfa_oracle_branch", "dfa_oracle_segment_probs",
                      "dfa_oracle_merge", "dfa_oracle_forward", "dfa_oracle_forward_rows",
-                     "dfa_oracle_num_threads"):
+                     "dfa_oracle_num_threads", "dfa_oracle_backward"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -154,6 +154,22 @@ def forward_rows(q, k, v, branches, scale, bhn, head_offsets=None):
     if rc != 0:
         raise ValueError("dfa_oracle_forward_rows: bad arguments")
     return out, lse
+
+
+def backward(q, k, v, dout, branches, scale, head_offsets=None):
+    """(dq, dk, dv) for a gradient dout of the merged output; all [B, N, H, D] fp64."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, N, H, D = q.shape
+    nb = len(branches)
+    w = np.ascontiguousarray([b[0] for b in branches], dtype=np.int32)
+    r = np.ascontiguousarray([b[1] for b in branches], dtype=np.int32)
+    offs = _offsets(head_offsets, nb, H)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    rc = _load().dfa_oracle_backward(_d(q), _d(k), _d(v), _d(dout), B, H, N, D, ctypes.c_double(scale), nb,
+                                     _i(w), _i(r), _i(offs), _d(dq), _d(dk), _d(dv))
+    if rc != 0:
+        raise ValueError("dfa_oracle_backward: bad arguments")
+    return dq, dk, dv
 
 
 # ---------------------------------------------------------------------------------------------

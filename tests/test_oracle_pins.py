@@ -398,3 +398,56 @@ def test_short_last_part_is_dense_attention_on_its_slice(oracle):
     out2, lse2 = oracle.forward(q, k, v, [(40, 1)], 0.9)
     o_ref, l_ref = dense_softmax_attention(q[0, :, 0], k[0, :, 0], v[0, :, 0], 0.9)
     assert np.abs(out2[0, :, 0] - o_ref).max() < 1e-13 and np.abs(lse2[0, 0] - l_ref).max() < 1e-13
+
+
+# ---------------------------------------------------------------- backward
+@pytest.mark.parametrize("N,branches,offs", [
+    (12, [(12, 1)], None),                                  # dense
+    (16, [(8, 2), (16, 4)], None),                          # overlapping key sets, uncovered rows
+    (15, [(4, 1), (6, 3), (32, 2)], [[0, 0], [2, 1], [1, 0]]),   # ragged parts
+])
+def test_backward_matches_central_differences_of_the_forward(oracle, N, branches, offs):
+    """Gradients of loss = sum(out * G) by central differences of the pinned forward, element by
+    element: pins every term of the backward (a wrong sign, a dropped delta term, a missing scale
+    or q and k swapped each fail it)."""
+    rng = np.random.default_rng(31)
+    B, H, D, scale, eps = 1, 2, 3, 0.6, 1e-5
+    q, k, v = (rng.standard_normal((B, N, H, D)) for _ in range(3))
+    G = rng.standard_normal((B, N, H, D))
+    dq, dk, dv = oracle.backward(q, k, v, G, branches, scale, head_offsets=offs)
+
+    def loss(qq, kk, vv):
+        out, _ = oracle.forward(qq, kk, vv, branches, scale, head_offsets=offs)
+        return float((out * G).sum())
+
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = x[idx]
+            x[idx] = old + eps
+            lp = loss(q, k, v)
+            x[idx] = old - eps
+            lm = loss(q, k, v)
+            x[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        assert np.abs(num - g).max() < 1e-7, (name, float(np.abs(num - g).max()))
+
+
+def test_backward_special_cases(oracle):
+    rng = np.random.default_rng(32)
+    # one key per part: out = v, so dv = dout and dq = dk = 0
+    q, k, v, G = (rng.standard_normal((2, 6, 2, 4)) for _ in range(4))
+    dq, dk, dv = oracle.backward(q, k, v, G, [(1, 1)], 1.3)
+    assert np.array_equal(dv, G) and np.all(dq == 0) and np.all(dk == 0)
+    # q = 0: uniform weights 1/n inside a part, so dv_j = mean of dout over the part and dk = 0
+    N, w = 12, 4
+    q0 = np.zeros((1, N, 1, 3)); k, v, G = (rng.standard_normal((1, N, 1, 3)) for _ in range(3))
+    dq, dk, dv = oracle.backward(q0, k, v, G, [(w, 1)], 0.8)
+    for lo in range(0, N, w):
+        assert np.abs(dv[0, lo:lo + w, 0] - G[0, lo:lo + w, 0].mean(axis=0)).max() < 1e-14
+    assert np.abs(dk).max() < 1e-14
+    # rows kept by no branch take and give no gradient
+    _, _, dv2 = oracle.backward(rng.standard_normal((1, 8, 1, 3)), k[:, :8], v[:, :8], G[:, :8], [(8, 2)], 0.8)
+    assert np.all(dv2[0, 1::2] == 0)
