@@ -112,6 +112,26 @@ int dfa_forward(const void *q, const void *k, const void *v,
                 void *out, float *lse, void *stream);
 
 /*
+ * Backward of dfa_forward: gradients with respect to q, k, v for a gradient dout of the merged
+ * output (lse takes no gradient).  The paper gives no backward pass; this is the chain rule on
+ * Eq. 2 and the branch merge: with P = exp(scale q_n.k_j - lse_n) per (branch, n, j) pair of
+ * the definition and delta_n = dout_n . out_n,  dv_j += P dout_n,  ds = P (dout_n . v_j - delta_n),
+ * dq_n += scale ds k_j,  dk_j += scale ds q_n.
+ *   q, k, v, strides, shapes, dt, scale, branches, head_offsets   exactly as passed to dfa_forward
+ *   out, lse       device, what dfa_forward returned (out dtype dt [B, N, H, D], lse fp32 [B, H, N])
+ *   dout           device, dtype dt, contiguous [B, N, H, D]
+ *   delta_ws       device, fp32 [B, H, N] workspace (receives dout . out per row)
+ *   dq, dk, dv     device, dtype dt, contiguous [B, N, H, D]; rows kept by no branch get 0
+ * fp32 vector arithmetic for both dtypes (bf16 rows are widened on load, results rounded to
+ * bf16); four launches on `stream`; uses the plan cache of dfa_forward.
+ */
+int dfa_backward(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                 const void *dout, dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                 int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                 const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
+                 float *delta_ws, void *dq, void *dk, void *dv, void *stream);
+
+/*
  * One branch, unmerged (Eq. 1-3 for a single (w, r)): out_b device fp32 [B, N, H, D]
  * (0 on rows the branch does not keep), lse_b device fp32 [B, H, N] (-inf there).
  * head_offsets host int32 [H] or NULL.  Inputs of dtype dt as in dfa_forward.

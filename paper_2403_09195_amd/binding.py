@@ -18,7 +18,7 @@ DFA_MAX_BRANCHES = 8
 EXPORTS = [
     "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_forward",
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
-    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack", "dfa_mfma_peak",
+    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack", "dfa_mfma_peak", "dfa_backward",
 ]
 
 
@@ -81,6 +81,8 @@ def lib():
         L.dfa_linear.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
         L.dfa_encoder_stack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, ctypes.POINTER(Branch), i32,
                                         _i32p, vp, vp, vp, vp]
+        L.dfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, ctypes.c_int,
+                                   f32, ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp, vp, vp]
         L.dfa_mfma_peak.argtypes = [i32, ctypes.POINTER(f32), ctypes.POINTER(f32)]
         for name in EXPORTS:
             if name != "dfa_error_string":
@@ -303,6 +305,28 @@ def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, workspac
                                    vp(qkv.data_ptr()), vp(attn.data_ptr()), vp(y.data_ptr()), _stream()),
            "dfa_encoder_stack")
     return y, qkv, attn
+
+
+def backward(q, k, v, out, lse, dout, branches, scale, head_offsets=None):
+    """(dq, dk, dv) of dfa_forward for a gradient dout of its output; all [B, N, H, D] of q's dtype."""
+    import torch
+    for t, nm in ((q, "q"), (k, "k"), (v, "v"), (out, "out"), (lse, "lse"), (dout, "dout")):
+        _gpu(t, nm)
+    B, N, H, D = q.shape
+    if not (out.is_contiguous() and dout.is_contiguous() and lse.is_contiguous()):
+        raise ValueError("backward: out, dout and lse must be contiguous")
+    if out.dtype != q.dtype or dout.dtype != q.dtype or lse.dtype != torch.float32:
+        raise TypeError("backward: out and dout must have q's dtype, lse fp32")
+    br, nb = _branches(branches)
+    dq, dk, dv = (torch.empty((B, N, H, D), dtype=q.dtype, device=q.device) for _ in range(3))
+    delta = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    vp = ctypes.c_void_p
+    _check(lib().dfa_backward(vp(q.data_ptr()), vp(k.data_ptr()), vp(v.data_ptr()), vp(out.data_ptr()),
+                              vp(lse.data_ptr()), vp(dout.data_ptr()), _strides(q), _strides(k), _strides(v),
+                              B, H, N, D, _dtype_code(q), ctypes.c_float(scale), br, nb, _i32_array(head_offsets),
+                              vp(delta.data_ptr()), vp(dq.data_ptr()), vp(dk.data_ptr()), vp(dv.data_ptr()), _stream()),
+           "dfa_backward")
+    return dq, dk, dv
 
 
 def mfma_peak(random_operands=True):

@@ -268,6 +268,41 @@ int dfa_scatter(const void* og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
                           static_cast<hipStream_t>(stream)) == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
 }
 
+int dfa_backward(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                 const void* dout, dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                 int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                 const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                 float* delta_ws, void* dq, void* dk, void* dv, void* stream) {
+    if (!q || !k || !v || !out || !lse || !dout || !delta_ws || !dq || !dk || !dv) return DFA_ERR_NULL;
+    int rc = check_common(B, H, N, D, dt);
+    if (rc != DFA_OK) return rc;
+    rc = check_branches(H, N, branches, nb, head_offsets);
+    if (rc != DFA_OK) return rc;
+    if (!std::isfinite(scale) || scale <= 0.f) return DFA_ERR_SHAPE;
+    const int es = elem_size(dt);
+    if (!aligned_rows(q, sq, es) || !aligned_rows(k, sk, es) || !aligned_rows(v, sv, es)) return DFA_ERR_ALIGN;
+    for (const void* ptr : {out, dout, (const void*)dq, (const void*)dk, (const void*)dv})
+        if (reinterpret_cast<uintptr_t>(ptr) % 16) return DFA_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(lse) % 4 || reinterpret_cast<uintptr_t>(delta_ws) % 4) return DFA_ERR_ALIGN;
+    try {
+        DevicePlan dp;
+        rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+        if (rc != DFA_OK) return rc;
+        BwdParams p;
+        p.q = q; p.k = k; p.v = v; p.out = out; p.dout = dout;
+        p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
+        p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
+        p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
+        p.lse = lse; p.delta = delta_ws; p.dq = dq; p.dk = dk; p.dv = dv;
+        p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
+        p.H = H; p.N = N; p.scale = scale;
+        return launch_bwd(p, dp.n_items, B, dt == DFA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess
+                   ? DFA_OK : DFA_ERR_LAUNCH;
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+}
+
 int dfa_linear(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                int64_t ldx, int64_t ldw, int64_t ldy, void* stream) {
     if (!x || !w || !y) return DFA_ERR_NULL;

@@ -33,6 +33,29 @@ struct FwdParams {
     float scale;        // multiplies q.k
 };
 
+// Arguments of the backward kernels.  out, dout, dq, dk, dv are contiguous [B, N, H, D].
+struct BwdParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    const void* out;
+    const void* dout;
+    int64_t sqb, sqn, sqh;
+    int64_t skb, skn, skh;
+    int64_t svb, svn, svh;
+    const float* lse;   // [B, H, N], merged, from the forward pass
+    float* delta;       // [B, H, N] workspace: dout . out per row
+    void* dq;
+    void* dk;
+    void* dv;
+    const Tile* tiles;
+    const int32_t* rows;
+    const KeySeg* segs;
+    const Item* items;
+    int32_t H, N;
+    float scale;
+};
+
 // Per-head start offsets of the stand-alone indexer / gather / scatter kernels, passed by
 // value: explicit tables are limited to kMaxExplicitHeads heads, h mod r has no limit.
 constexpr int kMaxExplicitHeads = 128;
@@ -53,6 +76,7 @@ __device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o
 // Launchers (defined in the .hip files); every one returns the hipError_t of the launch.
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
+hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st);
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                               int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st);
 hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,

@@ -1,0 +1,95 @@
+"""GPU parity of the backward entry point against the fp64 oracle (itself pinned by central
+differences of the forward).  The GPU backward is given the GPU forward's own out and lse."""
+import numpy as np
+import pytest
+
+from gpu_util import make_qkv, to_device, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2403_09195_amd import binding
+    binding.lib()
+    return binding
+
+
+def _dout(seed, shape, dtype):
+    from paper_2403_09195_amd import synth
+    st, ex = synth.tensor(seed, 7, shape, dtype)
+    return to_device(st), ex
+
+
+def _report(tag, got, ref):
+    """Returns (worst excess over the final bf16 rounding, mean-abs error), both relative to the rms."""
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    d = np.abs(got - ref)
+    excess = float((d - 2.0 ** -8 * np.abs(ref)).max())
+    print(f"[{tag}] max-abs {d.max():.3e} mean-abs {d.mean():.3e} (gradient rms {rms:.3e}), "
+          f"beyond the result's own rounding {excess:.3e}", flush=True)
+    return excess / rms, float(d.mean()) / rms
+
+
+CASES = [
+    (2, 256, 3, [(64, 2)], None),                                   # uncovered rows
+    (1, 512, 4, [(128, 1), (256, 2), (512, 4)], None),              # the workload's branch pattern, scaled down
+    (2, 300, 2, [(100, 3), (77, 1), (512, 5)], [[2, 0], [0, 0], [4, 1]]),   # ragged parts, explicit offsets
+]
+
+
+@pytest.mark.parametrize("Bsz,N,H,branches,offs", CASES)
+def test_backward_fp32(B, oracle, Bsz, N, H, branches, offs):
+    """fp32 path: sums of up to a few thousand fp32 products per gradient element; held to 2e-5 of the
+    largest gradient magnitude (measured about 1e-6)."""
+    (q, k, v), ex = make_qkv(500 + N, Bsz, N, H, 64, "f32")
+    g, ge = _dout(500 + N, (Bsz, N, H, 64), "f32")
+    out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125, head_offsets=offs)
+    rq, rk, rv = oracle.backward(*ex, ge, branches, 0.125, head_offsets=offs)
+    for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        err = np.abs(to_f64(got) - ref)
+        print(f"[f32 {name}] max-abs {err.max():.3e}, largest gradient {np.abs(ref).max():.3e}", flush=True)
+        assert err.max() <= 2e-5 * max(1.0, np.abs(ref).max())
+    _, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
+    dead = np.isneginf(l_ref).transpose(0, 2, 1)
+    for got in (dq, dk, dv):
+        assert np.all(to_f64(got)[dead] == 0.0)
+
+
+@pytest.mark.parametrize("Bsz,N,H,branches,offs", CASES)
+def test_backward_bf16(B, oracle, Bsz, N, H, branches, offs):
+    """bf16 path: fp32 arithmetic on bf16 operands; every gradient is rounded to bf16 (up to 2^-8 of its
+    own size) and delta = dout . out is taken from the bf16-rounded forward output, which perturbs
+    every ds of a row alike.  Bar: |err| <= 2^-8 |g| + 1e-2 rms(g) per element, mean-abs <= 2e-3 rms(g)."""
+    (q, k, v), ex = make_qkv(600 + N, Bsz, N, H, 64, "bf16")
+    g, ge = _dout(600 + N, (Bsz, N, H, 64), "bf16")
+    out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125, head_offsets=offs)
+    rq, rk, rv = oracle.backward(*ex, ge, branches, 0.125, head_offsets=offs)
+    for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        mx, mean = _report(f"bf16 {name}", to_f64(got), ref)
+        assert mx <= 1e-2 and mean <= 2e-3
+
+
+def test_backward_reads_strided_inputs_and_rejects_bad_arguments(B, oracle):
+    import torch
+    from paper_2403_09195_amd import synth
+    Bsz, N, H, D = 1, 256, 2, 64
+    branches = [(128, 1), (256, 2)]
+    st, ex = synth.tensor(701, 3, (Bsz, N, 3, H, D), "f32")
+    packed = to_device(st)
+    q, k, v = packed[:, :, 0], packed[:, :, 1], packed[:, :, 2]
+    g, ge = _dout(701, (Bsz, N, H, D), "f32")
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125)
+    rq, rk, rv = oracle.backward(ex[:, :, 0], ex[:, :, 1], ex[:, :, 2], ge, branches, 0.125)
+    for got, ref in ((dq, rq), (dk, rk), (dv, rv)):
+        assert np.abs(to_f64(got) - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max())
+    with pytest.raises(B.DfaError) as e:
+        B.backward(q, k, v, out, lse, g, [(128, 0)], 0.125)
+    assert e.value.code == -2
+    with pytest.raises(TypeError):
+        B.backward(q, k, v, out.bfloat16(), lse, g, branches, 0.125)
