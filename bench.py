@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="input-size sweep of the paper's ablation (256^2, 512^2, 1024^2 images; 6 and 12 heads): "
                          "dilated attention against dense attention in the same kernel (w = N, r = 1)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time dfa_backward (fp32 vector arithmetic, correctness-first kernels) on --workload")
     ap.add_argument("--layers", type=int, default=12, help="--stack: number of layers")
     ap.add_argument("--heads", type=int, default=12, help="--stack: heads of 64 (embed = 64 * heads)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -267,6 +269,31 @@ def main():
 
     if args.stages:
         print(json.dumps(stage_report(binding, torch, q, k, v, branches, scale, args.steps, args.warmup)))
+        return
+
+    if args.backward:
+        binding.forward(q, k, v, branches, scale, out=out, lse=lse)
+        g = torch.from_numpy(synth.tensor(cfg["seed"], 7, (Bsz, N, H, D), cfg["dtype"])[0]
+                             .view(np.int16 if cfg["dtype"] == "bf16" else np.float32)).cuda()
+        g = g.view(torch.bfloat16) if cfg["dtype"] == "bf16" else g
+        steps = max(1, min(args.steps, 5))
+        binding.backward(q, k, v, out, lse, g, branches, scale)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            binding.backward(q, k, v, out, lse, g, branches, scale)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        pairs = flops // (4 * D)
+        executed = pairs * 16 * D            # 3 + 2 + 3 dot products / row updates of D fused multiply-adds per pair
+        print(json.dumps({"metric": "dfa_backward ms per step (dq, dk, dv)", "value": ms, "unit": "ms", "steps": steps,
+                          "config": {"workload": args.workload}, "dtype": "f32 arithmetic on " + cfg["dtype"] + " operands",
+                          "useful_backward_TFLOP/s": 2.5 * flops / ms / 1e9,
+                          "roofline": {"bound": "alu", "achieved": executed / ms / 1e9, "peak": 157.3, "unit": "TFLOP/s",
+                                       "frac": executed / ms / 1e9 / 157.3,
+                                       "note": "executed fp32 flops: 16*D per (query, key) pair over the three kernels"}}))
         return
 
     for _ in range(args.warmup):
