@@ -120,10 +120,11 @@ int dfa_forward(const void *q, const void *k, const void *v,
  *   q, k, v, strides, shapes, dt, scale, branches, head_offsets   exactly as passed to dfa_forward
  *   out, lse       device, what dfa_forward returned (out dtype dt [B, N, H, D], lse fp32 [B, H, N])
  *   dout           device, dtype dt, contiguous [B, N, H, D]
- *   delta_ws       device, fp32 [B, H, N] workspace (receives dout . out per row)
+ *   delta_ws       device, fp32 [2][B, H, N] workspace (receives dout . out and lse * log2(e) per row)
  *   dq, dk, dv     device, dtype dt, contiguous [B, N, H, D]; rows kept by no branch get 0
- * fp32 vector arithmetic for both dtypes (bf16 rows are widened on load, results rounded to
- * bf16); four launches on `stream`; uses the plan cache of dfa_forward.
+ * dt = DFA_BF16: bf16 operands on the matrix cores, fp32 accumulation, P and dS rounded to bf16
+ * before their second products, gradients rounded to bf16.  dt = DFA_F32: fp32 vector arithmetic
+ * (correctness path).  Four launches on `stream`; uses the plan cache of dfa_forward.
  */
 int dfa_backward(const void *q, const void *k, const void *v, const void *out, const float *lse,
                  const void *dout, dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,

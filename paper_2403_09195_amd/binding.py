@@ -319,7 +319,7 @@ def backward(q, k, v, out, lse, dout, branches, scale, head_offsets=None):
         raise TypeError("backward: out and dout must have q's dtype, lse fp32")
     br, nb = _branches(branches)
     dq, dk, dv = (torch.empty((B, N, H, D), dtype=q.dtype, device=q.device) for _ in range(3))
-    delta = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    delta = torch.empty((2, B, H, N), dtype=torch.float32, device=q.device)
     vp = ctypes.c_void_p
     _check(lib().dfa_backward(vp(q.data_ptr()), vp(k.data_ptr()), vp(v.data_ptr()), vp(out.data_ptr()),
                               vp(lse.data_ptr()), vp(dout.data_ptr()), _strides(q), _strides(k), _strides(v),

@@ -1,6 +1,7 @@
 // C ABI of the dilated flash attention library: argument checks, launch-plan cache, launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <map>
@@ -284,6 +285,12 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
     for (const void* ptr : {out, dout, (const void*)dq, (const void*)dk, (const void*)dv})
         if (reinterpret_cast<uintptr_t>(ptr) % 16) return DFA_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(lse) % 4 || reinterpret_cast<uintptr_t>(delta_ws) % 4) return DFA_ERR_ALIGN;
+    // the copy lanes address a 64-row step with 32-bit byte offsets from its first row
+    for (int x = 0; x < nb; ++x) {
+        const int64_t widest = std::max(std::max(sq.n, sk.n), std::max(sv.n, (int64_t)H * D));
+        if (sq.n <= 0 || sk.n <= 0 || sv.n <= 0 || 64 * (int64_t)branches[x].r * widest * es + 128 >= ((int64_t)1 << 31))
+            return DFA_ERR_TOO_LARGE;
+    }
     try {
         DevicePlan dp;
         rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
@@ -293,7 +300,7 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
         p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
         p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
         p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
-        p.lse = lse; p.delta = delta_ws; p.dq = dq; p.dk = dk; p.dv = dv;
+        p.lse = lse; p.delta = delta_ws; p.lse2 = delta_ws + (int64_t)B * H * N; p.dq = dq; p.dk = dk; p.dv = dv;
         p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
         p.H = H; p.N = N; p.scale = scale;
         return launch_bwd(p, dp.n_items, B, dt == DFA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess

@@ -7,8 +7,9 @@
 //   dv_j += P dout_n,   ds = P (dout_n . v_j - delta_n),   dq_n += scale ds k_j,   dk_j += scale ds q_n.
 // P is recomputed from lse, nothing of the forward pass is stored besides out and lse.
 //
-// Correctness-first kernels in fp32 vector arithmetic for both input types (bf16 rows are widened
-// on load): the same launch plan as the forward pass, one lane per row of a tile.  In a
+// This file: the per-row preparation both precisions share (delta, and lse in base-2 units) and
+// the fp32 path, correctness-first kernels in fp32 vector arithmetic on the same launch plan as
+// the forward pass, one lane per row of a tile.  bf16 operands go to the matrix-core kernels.  In a
 // segment the kept rows are queries and keys alike, so a tile's key lists are also the lists of
 // queries that see its rows as keys: the dq kernel walks them as keys, the dk and dv kernels walk
 // them as queries, and no gradient needs an atomic or a second pass over partial sums.
@@ -77,10 +78,11 @@ __device__ __forceinline__ void axpy_row(float s, const float* b, float (&acc)[k
     }
 }
 
-// delta[b][h][n] = dout[b][n][h][:] . out[b][n][h][:]; 16 lanes per row, 4 d each
+// delta[b][h][n] = dout[b][n][h][:] . out[b][n][h][:] and lse2 = lse * log2(e); 16 lanes per row, 4 d each
 template <typename T>
 __global__ __launch_bounds__(256)
-void bwd_delta_kernel(const T* out, const T* dout, float* delta, int32_t H, int32_t N, int64_t rows) {
+void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* delta, float* lse2, int32_t H, int32_t N,
+                      int64_t rows) {
     const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t rowid = x >> 4;                                   // (b, n, h) flattened
     const int part = (int)(x & 15);
@@ -94,7 +96,9 @@ void bwd_delta_kernel(const T* out, const T* dout, float* delta, int32_t H, int3
     if (rowid < rows && part == 0) {
         const int32_t h = (int32_t)(rowid % H);
         const int64_t bn = rowid / H;
-        delta[((bn / N) * H + h) * N + bn % N] = s;
+        const int64_t at = ((bn / N) * H + h) * N + bn % N;
+        delta[at] = s;
+        lse2[at] = lse[at] * kLog2e;
     }
 }
 
@@ -204,10 +208,11 @@ template <typename T>
 hipError_t launch_all(const BwdParams& p, int n_items, int32_t B, hipStream_t st) {
     const int64_t rows = (int64_t)B * p.N * p.H;
     hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.delta, p.H, p.N, rows);
-    hipLaunchKernelGGL((bwd_kernel<T, 0>), dim3(n_items), dim3(256), 0, st, p);
-    hipLaunchKernelGGL((bwd_kernel<T, 1>), dim3(n_items), dim3(256), 0, st, p);
-    hipLaunchKernelGGL((bwd_kernel<T, 2>), dim3(n_items), dim3(256), 0, st, p);
+                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.delta, p.lse2, p.H, p.N, rows);
+    if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);
+    hipLaunchKernelGGL((bwd_kernel<float, 0>), dim3(n_items), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((bwd_kernel<float, 1>), dim3(n_items), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((bwd_kernel<float, 2>), dim3(n_items), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

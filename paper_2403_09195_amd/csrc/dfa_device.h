@@ -45,6 +45,7 @@ struct BwdParams {
     int64_t svb, svn, svh;
     const float* lse;   // [B, H, N], merged, from the forward pass
     float* delta;       // [B, H, N] workspace: dout . out per row
+    float* lse2;        // [B, H, N] workspace: lse * log2(e) per row
     void* dq;
     void* dk;
     void* dv;
@@ -77,6 +78,7 @@ __device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st);
+hipError_t launch_bwd_bf16(const BwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                               int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st);
 hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,

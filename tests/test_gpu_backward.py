@@ -61,9 +61,11 @@ def test_backward_fp32(B, oracle, Bsz, N, H, branches, offs):
 
 @pytest.mark.parametrize("Bsz,N,H,branches,offs", CASES)
 def test_backward_bf16(B, oracle, Bsz, N, H, branches, offs):
-    """bf16 path: fp32 arithmetic on bf16 operands; every gradient is rounded to bf16 (up to 2^-8 of its
-    own size) and delta = dout . out is taken from the bf16-rounded forward output, which perturbs
-    every ds of a row alike.  Bar: |err| <= 2^-8 |g| + 1e-2 rms(g) per element, mean-abs <= 2e-3 rms(g)."""
+    """bf16 path (matrix cores): P and dS are rounded to bf16 before their second products, as the
+    forward rounds P (each term off by up to 2^-9 of itself, random in sign), delta = dout . out is
+    taken from the bf16-rounded forward output, and every gradient is rounded to bf16 (up to 2^-8 of
+    its own size).  Bar, the forward's figures taken relative to the gradient's rms:
+    |err| <= 2^-8 |g| + 2e-2 rms(g) per element, mean-abs <= 2e-3 rms(g)."""
     (q, k, v), ex = make_qkv(600 + N, Bsz, N, H, 64, "bf16")
     g, ge = _dout(600 + N, (Bsz, N, H, 64), "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
@@ -71,7 +73,7 @@ def test_backward_bf16(B, oracle, Bsz, N, H, branches, offs):
     rq, rk, rv = oracle.backward(*ex, ge, branches, 0.125, head_offsets=offs)
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
         mx, mean = _report(f"bf16 {name}", to_f64(got), ref)
-        assert mx <= 1e-2 and mean <= 2e-3
+        assert mx <= 2e-2 and mean <= 2e-3
 
 
 def test_backward_reads_strided_inputs_and_rejects_bad_arguments(B, oracle):
