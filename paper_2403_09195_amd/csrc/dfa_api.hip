@@ -285,6 +285,8 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
     for (const void* ptr : {out, dout, (const void*)dq, (const void*)dk, (const void*)dv})
         if (reinterpret_cast<uintptr_t>(ptr) % 16) return DFA_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(lse) % 4 || reinterpret_cast<uintptr_t>(delta_ws) % 4) return DFA_ERR_ALIGN;
+    rc = check_stage_grid(B, H, N);          // the per-row preparation carries b on the grid
+    if (rc != DFA_OK) return rc;
     // the copy lanes address a 64-row step with 32-bit byte offsets from its first row
     for (int x = 0; x < nb; ++x) {
         const int64_t widest = std::max(std::max(sq.n, sk.n), std::max(sv.n, (int64_t)H * D));

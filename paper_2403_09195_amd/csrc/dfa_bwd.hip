@@ -78,25 +78,27 @@ __device__ __forceinline__ void axpy_row(float s, const float* b, float (&acc)[k
     }
 }
 
-// delta[b][h][n] = dout[b][n][h][:] . out[b][n][h][:] and lse2 = lse * log2(e); 16 lanes per row, 4 d each
+// delta[b][h][n] = dout[b][n][h][:] . out[b][n][h][:] and lse2 = lse * log2(e); 16 lanes per row, 4 d each.
+// grid = (16 * rows of one image / 256, B): one image is indexed with 32-bit arithmetic.
 template <typename T>
 __global__ __launch_bounds__(256)
-void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* delta, float* lse2, int32_t H, int32_t N,
-                      int64_t rows) {
-    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t rowid = x >> 4;                                   // (b, n, h) flattened
-    const int part = (int)(x & 15);
+void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* delta, float* lse2, int32_t H, int32_t N) {
+    const uint32_t x = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t t = x >> 4;                                       // n * H + h
+    const int part = (int)(x & 15u);
+    const bool in = t < (uint32_t)N * (uint32_t)H;
+    const int64_t b = blockIdx.y;
+    const int64_t rowid = b * N * H + t;                             // (b, n, h) flattened
     float s = 0.f;
-    if (rowid < rows) {
+    if (in) {
         const float4 a = load4<T>(out + rowid * kD + 4 * part), g = load4<T>(dout + rowid * kD + 4 * part);
         s = (a.x * g.x + a.y * g.y) + (a.z * g.z + a.w * g.w);
     }
 #pragma unroll
     for (int m = 8; m >= 1; m >>= 1) s += __shfl_xor(s, m, 16);
-    if (rowid < rows && part == 0) {
-        const int32_t h = (int32_t)(rowid % H);
-        const int64_t bn = rowid / H;
-        const int64_t at = ((bn / N) * H + h) * N + bn % N;
+    if (in && part == 0) {
+        const uint32_t n = t / (uint32_t)H, h = t - n * (uint32_t)H;
+        const int64_t at = (b * H + h) * N + n;
         delta[at] = s;
         lse2[at] = lse[at] * kLog2e;
     }
@@ -206,9 +208,8 @@ void bwd_kernel(const BwdParams p) {
 
 template <typename T>
 hipError_t launch_all(const BwdParams& p, int n_items, int32_t B, hipStream_t st) {
-    const int64_t rows = (int64_t)B * p.N * p.H;
-    hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.delta, p.lse2, p.H, p.N, rows);
+    hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)(((int64_t)p.N * p.H * 16 + 255) / 256), B), dim3(256), 0, st,
+                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.delta, p.lse2, p.H, p.N);
     if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);
     hipLaunchKernelGGL((bwd_kernel<float, 0>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 1>), dim3(n_items), dim3(256), 0, st, p);
