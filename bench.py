@@ -287,7 +287,8 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         pairs = flops // (4 * D)
-        executed = pairs * 16 * D            # 3 + 2 + 3 dot products / row updates of D fused multiply-adds per pair
+        # products of 2*D flops per pair: bf16 path 3 (dq kernel) + 4 (dk and dv together), fp32 path 3 + 2 + 3
+        executed = pairs * (14 if cfg["dtype"] == "bf16" else 16) * D
         mfma = cfg["dtype"] == "bf16"
         peak = MFMA_BF16_PEAK_TFLOPS if mfma else 157.3
         print(json.dumps({"metric": "dfa_backward ms per step (dq, dk, dv)", "value": ms, "unit": "ms", "steps": steps,
@@ -296,9 +297,9 @@ def main():
                           "useful_backward_TFLOP/s": 2.5 * flops / ms / 1e9,
                           "roofline": {"bound": "mfma" if mfma else "alu", "achieved": executed / ms / 1e9, "peak": peak,
                                        "unit": "TFLOP/s", "frac": executed / ms / 1e9 / peak,
-                                       "note": "executed flops: 8 products of 2*D per (query, key) pair over the three "
-                                               "kernels (3 for dq, 2 for dv, 3 for dk: scores are recomputed in each); "
-                                               "useful = 5 products"}}))
+                                       "note": "executed flops: products of 2*D per (query, key) pair: 3 in the dq kernel, 4 in the "
+                                               "dk/dv kernel (bf16), 3 + 2 + 3 in the fp32 kernels: scores are recomputed in "
+                                               "each kernel; useful = 5 products"}}))
         return
 
     for _ in range(args.warmup):

@@ -5,8 +5,8 @@
 // pair of the definition and delta_n = dout_n . out_n:
 //   dv_j += P dout_n,   ds = P (dout_n . v_j - delta_n),   dq_n += scale ds k_j,   dk_j += scale ds q_n.
 //
-// Three launches on the forward's plan, one per gradient; a workgroup owns a tile of up to 256
-// rows (4 waves x 64 rows) and walks the tile's lists 64 rows at a time.  In a segment the kept
+// Two launches on the forward's plan, one for dq and one for dk and dv together; a workgroup owns
+// a tile of up to 256 rows and walks the tile's lists 64 rows at a time.  In a segment the kept
 // rows are queries and keys alike, so the lists are the tile's keys when its rows act as
 // queries (dq) and the queries that see its rows when they act as keys (dk, dv): no gradient
 // needs an atomic.  The rows of the tile stay in registers as B operands; the walked rows go
@@ -19,8 +19,8 @@
 //               of the first product's result is the contraction order sigma fixes).
 // Per 32 walked rows:
 //   dq:  S^T = K~ Q^T, dP^T = V~ dO^T, dS^T = P (dP - delta) scale, dQ^T += K~^T dS^T
-//   dv:  S   = Q~ K^T, P = exp2(..),                               dV^T += dO~^T P
-//   dk:  S   = Q~ K^T, dP = dO~ V^T, dS = P (dP - delta) scale,    dK^T += Q~^T dS
+//   dk, dv:  S = Q~ K^T, dP = dO~ V^T, P = exp2(..), dS = P (dP - delta) scale,
+//            dV^T += dO~^T P,  dK^T += Q~^T dS
 // (~ marks the walked rows).  lse and delta of the walked queries travel with the rows as 4-byte
 // copies.  P is recomputed from lse; there is no online softmax and no rescaling here.
 #include "dfa_device.h"
@@ -98,17 +98,13 @@ __device__ __forceinline__ void pack_block(const float (&x)[16], u32x4 (&pb)[2])
     }
 }
 
-// kMode 0: dq   (tile rows are queries; walked: K in A and T layout, V in A layout)
-// kMode 1: dv   (tile rows are keys;    walked: Q in A layout, dO in T layout, lse)
-// kMode 2: dk   (tile rows are keys;    walked: Q in A and T layout, dO in A layout, lse, delta)
-template <int kMode>
+// dq of a tile: its rows are queries, the lists are walked as keys (K in "A" and "T" layout, V in "A"
+// layout).  Four waves of 64 rows each.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void bwd_bf16_kernel(const BwdParams p) {
-    constexpr int kTensors = kMode == 1 ? 2 : 3;
-    constexpr int kScalars = kMode == 0 ? 0 : kMode;                 // lse (modes 1, 2), delta (mode 2)
-    constexpr int kCopies = 2 * kTensors + kScalars;                 // per wave per stage
+void bwd_dq_bf16_kernel(const BwdParams p) {
+    constexpr int kTensors = 3;
+    constexpr int kCopies = 2 * kTensors;                            // per wave per stage
     __shared__ __attribute__((aligned(1024))) uint16_t t_lds[kTensors][kBwdStages][kStageElems];
-    __shared__ __attribute__((aligned(256))) float sc_lds[2][kBwdStages][kKeyTile];
     __shared__ int32_t row_idx[kTileRows];
     __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
 
@@ -123,7 +119,7 @@ void bwd_bf16_kernel(const BwdParams p) {
     if (tid < tile.nseg) seg_lds[tid] = p.segs[tile.seg_begin + tid];
     __syncthreads();
 
-    uint16_t* const grad = static_cast<uint16_t*>(kMode == 0 ? p.dq : kMode == 1 ? p.dv : p.dk);
+    uint16_t* const grad = static_cast<uint16_t*>(p.dq);
     const int64_t out_bh = (int64_t)b * p.N * p.H + h;   // in rows of a contiguous [B,N,H,D] tensor; row n adds n * H
 
     if (tile.nseg == 0) {
@@ -163,26 +159,13 @@ void bwd_bf16_kernel(const BwdParams p) {
         n_steps += (__builtin_amdgcn_readfirstlane(seg_lds[s].count) + kKeyTile - 1) / kKeyTile;
 
     const uint32_t t_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &t_lds[0][0][0]);
-    const uint32_t sc_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &sc_lds[0][0][0]);
     constexpr uint32_t kStageBytes = kStageElems * 2, kTensorBytes = kBwdStages * kStageBytes;
 
     auto issue = [&](const KeyCursor& c, int slot) {
         const uint32_t st = t_addr + slot * kStageBytes;
-        if (kMode == 0) {
-            issue_tensor<true>(kp, p.skn, c, cl, wave, st);
-            issue_tensor<true>(vp, p.svn, c, cl, wave, st + kTensorBytes);
-            issue_tensor<false>(kp, p.skn, c, cl, wave, st + 2 * kTensorBytes);
-        } else if (kMode == 1) {
-            issue_tensor<true>(qp, p.sqn, c, cl, wave, st);
-            issue_tensor<false>(gp, g_pitch, c, cl, wave, st + kTensorBytes);
-            issue_scalars(lse2_bh, c, lane, sc_addr + slot * (kKeyTile * 4));
-        } else {
-            issue_tensor<true>(qp, p.sqn, c, cl, wave, st);
-            issue_tensor<true>(gp, g_pitch, c, cl, wave, st + kTensorBytes);
-            issue_tensor<false>(qp, p.sqn, c, cl, wave, st + 2 * kTensorBytes);
-            issue_scalars(lse2_bh, c, lane, sc_addr + slot * (kKeyTile * 4));
-            issue_scalars(delta_bh, c, lane, sc_addr + (kBwdStages + slot) * (kKeyTile * 4));
-        }
+        issue_tensor<true>(kp, p.skn, c, cl, wave, st);
+        issue_tensor<true>(vp, p.svn, c, cl, wave, st + kTensorBytes);
+        issue_tensor<false>(kp, p.skn, c, cl, wave, st + 2 * kTensorBytes);
     };
 
     // first two stages on their way before anything else
@@ -199,25 +182,18 @@ void bwd_bf16_kernel(const BwdParams p) {
     }
 
     // ---- the tile's own rows as B operands (16 d x 32 rows): lane (j, g) holds row j, d 16*kk + 8*g .. +7
-    bf16x8 own0[2][4], own1[2][4];       // dq: q, dout; dv: k; dk: k, v
-    float my_l2[2] = {0.f, 0.f}, my_delta[2] = {0.f, 0.f};
+    bf16x8 qf[2][4], gf[2][4];           // q and dout of the wave's two 32-row blocks
+    float my_l2[2], my_delta[2];
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
         const int64_t row = row_idx[wave * 64 + blk * 32 + j];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            if (kMode == 0) {
-                own0[blk][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
-                own1[blk][kk] = *reinterpret_cast<const bf16x8*>(gp + row * g_pitch + 16 * kk + 8 * g);
-            } else {
-                own0[blk][kk] = *reinterpret_cast<const bf16x8*>(kp + row * p.skn + 16 * kk + 8 * g);
-                if (kMode == 2) own1[blk][kk] = *reinterpret_cast<const bf16x8*>(vp + row * p.svn + 16 * kk + 8 * g);
-            }
+            qf[blk][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
+            gf[blk][kk] = *reinterpret_cast<const bf16x8*>(gp + row * g_pitch + 16 * kk + 8 * g);
         }
-        if (kMode == 0) {
-            my_l2[blk] = lse2_bh[row];
-            my_delta[blk] = delta_bh[row];
-        }
+        my_l2[blk] = lse2_bh[row];
+        my_delta[blk] = delta_bh[row];
     }
     // pin them: the compiler then waits for these loads here and places no vector-memory wait of
     // its own inside the main loop (it cannot see the copies, and its wait would drain them)
@@ -225,13 +201,11 @@ void bwd_bf16_kernel(const BwdParams p) {
     for (int blk = 0; blk < 2; ++blk) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            asm volatile("" : "+v"(own0[blk][kk]));
-            if (kMode != 1) asm volatile("" : "+v"(own1[blk][kk]));
+            asm volatile("" : "+v"(qf[blk][kk]));
+            asm volatile("" : "+v"(gf[blk][kk]));
         }
-        if (kMode == 0) {
-            asm volatile("" : "+v"(my_l2[blk]));
-            asm volatile("" : "+v"(my_delta[blk]));
-        }
+        asm volatile("" : "+v"(my_l2[blk]));
+        asm volatile("" : "+v"(my_delta[blk]));
     }
 
     const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale * kLog2e)));
@@ -257,86 +231,43 @@ void bwd_bf16_kernel(const BwdParams p) {
         }
         const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
         if (wave_live) {
-            const uint16_t* const ta = t_lds[0][slot];
-            const uint16_t* const tb = t_lds[1][slot];
-            const uint16_t* const tc = t_lds[kTensors - 1][slot];
 #pragma unroll
-            for (int ws = 0; ws < 2; ++ws) {                   // 32 walked rows at a time
+            for (int ws = 0; ws < 2; ++ws) {                   // 32 walked keys at a time
                 const int nv = nvalid - 32 * ws;
-                const uint16_t* const a_blk = ta + 32 * ws * kRowElems;
-                u32x4 pb[2][2];                                // [own block][16-row step], packed bf16 pairs
-                if (kMode == 0) {
-                    floatx16 s[2], dp[2];
+                const uint16_t* const ka = t_lds[0][slot] + 32 * ws * kRowElems;
+                const uint16_t* const va = t_lds[1][slot] + 32 * ws * kRowElems;
+                u32x4 pb[2][2];                                // [own block][16-key step], packed bf16 pairs
+                floatx16 s[2], dp[2];
 #pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) {
-                        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(a_blk + (frag_a ^ (16 * kk)));
-                        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(tb + 32 * ws * kRowElems + (frag_a ^ (16 * kk)));
-#pragma unroll
-                        for (int blk = 0; blk < 2; ++blk) {
-                            s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, own0[blk][kk], kk == 0 ? zero16() : s[blk], 0, 0, 0);
-                            dp[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, own1[blk][kk], kk == 0 ? zero16() : dp[blk], 0, 0, 0);
-                        }
-                    }
+                for (int kk = 0; kk < 4; ++kk) {
+                    const bf16x8 kfr = *reinterpret_cast<const bf16x8*>(ka + (frag_a ^ (16 * kk)));
+                    const bf16x8 vfr = *reinterpret_cast<const bf16x8*>(va + (frag_a ^ (16 * kk)));
 #pragma unroll
                     for (int blk = 0; blk < 2; ++blk) {
-                        if (nv < 32) mask_rows(s[blk], g, nv);
-                        float ds[16];
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float pr = __builtin_amdgcn_exp2f(fmaf(s[blk][v], c, -my_l2[blk]));
-                            ds[v] = pr * (dp[blk][v] - my_delta[blk]) * scale;
-                        }
-                        pack_block(ds, pb[blk]);
-                    }
-                } else {
-                    // lse (and delta) of the walked queries: register v is block position 16*(v/8) + 8*g + v%8
-                    float l2r[16], dlr[16];
-                    {
-                        const float* lp = &sc_lds[0][slot][32 * ws + 8 * g];
-                        const float* dl = &sc_lds[1][slot][32 * ws + 8 * g];
-#pragma unroll
-                        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                            for (int e = 0; e < 8; e += 4) {
-                                const float4 x = *reinterpret_cast<const float4*>(lp + 16 * hf + e);
-                                l2r[8 * hf + e] = x.x; l2r[8 * hf + e + 1] = x.y; l2r[8 * hf + e + 2] = x.z; l2r[8 * hf + e + 3] = x.w;
-                                if (kMode == 2) {
-                                    const float4 y = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
-                                    dlr[8 * hf + e] = y.x; dlr[8 * hf + e + 1] = y.y; dlr[8 * hf + e + 2] = y.z; dlr[8 * hf + e + 3] = y.w;
-                                }
-                            }
-                    }
-#pragma unroll
-                    for (int blk = 0; blk < 2; ++blk) {        // one own block at a time keeps the register count down
-                        floatx16 s, dp;
-#pragma unroll
-                        for (int kk = 0; kk < 4; ++kk) {
-                            const bf16x8 qf = *reinterpret_cast<const bf16x8*>(a_blk + (frag_a ^ (16 * kk)));
-                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, own0[blk][kk], kk == 0 ? zero16() : s, 0, 0, 0);
-                            if (kMode == 2) {
-                                const bf16x8 gf = *reinterpret_cast<const bf16x8*>(tb + 32 * ws * kRowElems + (frag_a ^ (16 * kk)));
-                                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, own1[blk][kk], kk == 0 ? zero16() : dp, 0, 0, 0);
-                            }
-                        }
-                        if (nv < 32) mask_rows(s, g, nv);
-                        float x[16];
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float pr = __builtin_amdgcn_exp2f(fmaf(s[v], c, -l2r[v]));
-                            x[v] = kMode == 1 ? pr : pr * (dp[v] - dlr[v]) * scale;
-                        }
-                        pack_block(x, pb[blk]);
+                        s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, qf[blk][kk], kk == 0 ? zero16() : s[blk], 0, 0, 0);
+                        dp[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, gf[blk][kk], kk == 0 ? zero16() : dp[blk], 0, 0, 0);
                     }
                 }
-                // second product: acc^T[d][own row] += walked^T[d][walked row] . packed[walked row][own row]
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    if (nv < 32) mask_rows(s[blk], g, nv);
+                    float ds[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float pr = __builtin_amdgcn_exp2f(fmaf(s[blk][v], c, -my_l2[blk]));
+                        ds[v] = pr * (dp[blk][v] - my_delta[blk]) * scale;
+                    }
+                    pack_block(ds, pb[blk]);
+                }
+                // dQ^T[d][query] += K~^T[d][key] . dS^T[key][query]
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
                     for (int st = 0; st < 2; ++st) {
-                        const bf16x8 tf = read_v_frag(tc + (32 * ws + 16 * st) * kRowElems + frag_t + 32 * db);
+                        const bf16x8 kt = read_v_frag(t_lds[2][slot] + (32 * ws + 16 * st) * kRowElems + frag_t + 32 * db);
 #pragma unroll
                         for (int blk = 0; blk < 2; ++blk)
-                            acc[db][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, __builtin_bit_cast(bf16x8, pb[blk][st]), acc[db][blk], 0, 0, 0);
+                            acc[db][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, __builtin_bit_cast(bf16x8, pb[blk][st]), acc[db][blk], 0, 0, 0);
                     }
             }
         }
@@ -374,12 +305,227 @@ void bwd_bf16_kernel(const BwdParams p) {
     }
 }
 
+// dk and dv of a tile in one walk over its query lists.  Eight waves of 32 rows each (both
+// gradients of 64 rows would not fit a wave's registers): the scores are computed once for both,
+// and the walked Q and dO rows are copied once, each in both layouts.
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void bwd_dkdv_bf16_kernel(const BwdParams p) {
+    constexpr int kTensors = 4;                                      // Q "A", dO "A", Q "T", dO "T"
+    constexpr int kCopies = kTensors + 2;                            // per wave per stage, with lse and delta
+    __shared__ __attribute__((aligned(1024))) uint16_t t_lds[kTensors][kBwdStages][kStageElems];
+    __shared__ __attribute__((aligned(256))) float sc_lds[2][kBwdStages][kKeyTile];
+    __shared__ int32_t row_idx[kTileRows];
+    __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
+
+    const Item item = p.items[blockIdx.x];
+    if (item.tile < 0) return;
+    const Tile tile = p.tiles[item.tile];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int h = tile.h, b = item.b;
+
+    if (tid < kTileRows) row_idx[tid] = p.rows[tile.row_begin + min(tid, tile.nrows - 1)];
+    if (tid < tile.nseg) seg_lds[tid] = p.segs[tile.seg_begin + tid];
+    __syncthreads();
+
+    uint16_t* const grad_k = static_cast<uint16_t*>(p.dk);
+    uint16_t* const grad_v = static_cast<uint16_t*>(p.dv);
+    const int64_t out_bh = (int64_t)b * p.N * p.H + h;   // in rows of a contiguous [B,N,H,D] tensor; row n adds n * H
+
+    if (tile.nseg == 0) {
+        // rows that no branch keeps take and give no gradient
+        constexpr int kChunks = kD * 2 / 16;
+        for (int x = tid; x < tile.nrows * kChunks; x += 512) {
+            const int rr = x / kChunks, ch = x % kChunks;
+            const int64_t at = (out_bh + (int64_t)row_idx[rr] * p.H) * kD;
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(grad_k + at) + 16 * ch) = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(grad_v + at) + 16 * ch) = u32x4{0u, 0u, 0u, 0u};
+        }
+        return;
+    }
+
+    const uint16_t* const qp = static_cast<const uint16_t*>(p.q) + (int64_t)b * p.sqb + (int64_t)h * p.sqh;
+    const uint16_t* const kp = static_cast<const uint16_t*>(p.k) + (int64_t)b * p.skb + (int64_t)h * p.skh;
+    const uint16_t* const vp = static_cast<const uint16_t*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
+    const uint16_t* const gp = static_cast<const uint16_t*>(p.dout) + out_bh * kD;          // row n at n * H * D
+    const int64_t g_pitch = (int64_t)p.H * kD;
+    const float* const delta_bh = p.delta + ((int64_t)b * p.H + h) * p.N;
+    const float* const lse2_bh = p.lse2 + ((int64_t)b * p.H + h) * p.N;
+
+    // one 1 KB copy per wave and tensor: wave w fills LDS rows rho = 8w .. 8w+7, lane L lands at row L/8, chunk L%8
+    const int rho = 8 * wave + (lane >> 3);
+    const int a_pos = (rho & 0x33) | ((rho & 4) << 1) | ((rho & 8) >> 1);      // sigma(rho)
+    const int a_chunk = 16 * ((lane & 7) ^ k_swizzle(rho));
+    const int t_chunk = 16 * (lane & 7);
+    const int frag_a = j * kRowElems + 8 * (g ^ k_swizzle(j));
+    const int frag_t = (((lane & 15) >> 2) + 8 * g) * kRowElems + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+    int n_steps = 0;
+    for (int s = 0; s < tile.nseg; ++s)
+        n_steps += (__builtin_amdgcn_readfirstlane(seg_lds[s].count) + kKeyTile - 1) / kKeyTile;
+
+    const uint32_t t_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &t_lds[0][0][0]);
+    const uint32_t sc_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &sc_lds[0][0][0]);
+    constexpr uint32_t kStageBytes = kStageElems * 2, kTensorBytes = kBwdStages * kStageBytes;
+
+    auto issue = [&](const KeyCursor& c, int slot) {
+        const int j0 = c.t * kKeyTile;
+        const int room = c.count - 1 - j0;   // positions past the end of the list re-read its last row
+        const int64_t first = kept_row(c.key0, c.stride, j0);
+        const uint32_t qpitch = (uint32_t)(c.stride * p.sqn * 2), gpitch = (uint32_t)(c.stride * g_pitch * 2);
+        const void* qb = uniform_ptr(qp + first * p.sqn);
+        const void* gb = uniform_ptr(gp + first * g_pitch);
+        const uint32_t st = t_addr + slot * kStageBytes + wave * 1024u;
+        const uint32_t pa = (uint32_t)min(a_pos, room), pt = (uint32_t)min(rho, room);
+        copy16_to_lds(qb, pa * qpitch + a_chunk, st);
+        copy16_to_lds(gb, pa * gpitch + a_chunk, st + kTensorBytes);
+        copy16_to_lds(qb, pt * qpitch + t_chunk, st + 2 * kTensorBytes);
+        copy16_to_lds(gb, pt * gpitch + t_chunk, st + 3 * kTensorBytes);
+        issue_scalars(lse2_bh, c, lane, sc_addr + slot * (kKeyTile * 4));
+        issue_scalars(delta_bh, c, lane, sc_addr + (kBwdStages + slot) * (kKeyTile * 4));
+    };
+
+    KeyCursor pf;
+    pf.s = 0;
+    pf.t = 0;
+    cursor_load(pf, seg_lds);
+    KeyCursor cur = pf;
+    issue(pf, 0);
+    cursor_next(pf, seg_lds, tile.nseg);
+    if (n_steps > 1) {
+        issue(pf, 1);
+        cursor_next(pf, seg_lds, tile.nseg);
+    }
+
+    // the wave's own 32 rows as B operands (16 d x 32 rows): lane (j, g) holds row j, d 16*kk + 8*g .. +7
+    bf16x8 kf[4], vf[4];
+    {
+        const int64_t row = row_idx[wave * 32 + j];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            kf[kk] = *reinterpret_cast<const bf16x8*>(kp + row * p.skn + 16 * kk + 8 * g);
+            vf[kk] = *reinterpret_cast<const bf16x8*>(vp + row * p.svn + 16 * kk + 8 * g);
+        }
+        // pinned: the compiler waits for these loads here and places no vector-memory wait of its own in the loop
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            asm volatile("" : "+v"(kf[kk]));
+            asm volatile("" : "+v"(vf[kk]));
+        }
+    }
+
+    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale * kLog2e)));
+    const float scale = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale)));
+
+    floatx16 dk_acc[2], dv_acc[2];         // [d block], transposed: lane = own row
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+        dk_acc[db] = zero16();
+        dv_acc[db] = zero16();
+    }
+    const bool wave_live = wave * 32 < tile.nrows;
+
+    int slot = 0;
+    for (int i = 0; i < n_steps; ++i) {
+        if (i == 0 || i + 1 >= n_steps) wait_vmcnt<0>(); else wait_vmcnt<kCopies>();
+        __syncthreads();       // every wave's share is in LDS, and everyone is done with stage i-1
+        if (i + 2 < n_steps) {
+            issue(pf, slot == 0 ? 2 : slot - 1);               // (slot + 2) % 3
+            cursor_next(pf, seg_lds, tile.nseg);
+        }
+        const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+        if (wave_live) {
+#pragma unroll
+            for (int ws = 0; ws < 2; ++ws) {                   // 32 walked queries at a time
+                const int nv = nvalid - 32 * ws;
+                const uint16_t* const qa = t_lds[0][slot] + 32 * ws * kRowElems;
+                const uint16_t* const ga = t_lds[1][slot] + 32 * ws * kRowElems;
+                floatx16 s, dp;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qa + (frag_a ^ (16 * kk)));
+                    const bf16x8 gf = *reinterpret_cast<const bf16x8*>(ga + (frag_a ^ (16 * kk)));
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kk], kk == 0 ? zero16() : s, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[kk], kk == 0 ? zero16() : dp, 0, 0, 0);
+                }
+                if (nv < 32) mask_rows(s, g, nv);
+                // lse and delta of the walked queries: register v is block position 16*(v/8) + 8*g + v%8
+                float pr[16], ds[16];
+                {
+                    const float* lp = &sc_lds[0][slot][32 * ws + 8 * g];
+                    const float* dl = &sc_lds[1][slot][32 * ws + 8 * g];
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                        for (int e = 0; e < 8; e += 4) {
+                            const float4 l2 = *reinterpret_cast<const float4*>(lp + 16 * hf + e);
+                            const float4 dd = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
+                            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dda[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                const int v = 8 * hf + e + x;
+                                pr[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, -l2a[x]));
+                                ds[v] = pr[v] * (dp[v] - dda[x]) * scale;
+                            }
+                        }
+                }
+                u32x4 pp[2], ps[2];
+                pack_block(pr, pp);
+                pack_block(ds, ps);
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int st = 0; st < 2; ++st) {
+                        const int off = (32 * ws + 16 * st) * kRowElems + frag_t + 32 * db;
+                        const bf16x8 qt = read_v_frag(t_lds[2][slot] + off);
+                        const bf16x8 gt = read_v_frag(t_lds[3][slot] + off);
+                        dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, __builtin_bit_cast(bf16x8, pp[st]), dv_acc[db], 0, 0, 0);
+                        dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, __builtin_bit_cast(bf16x8, ps[st]), dk_acc[db], 0, 0, 0);
+                    }
+            }
+        }
+        cursor_next(cur, seg_lds, tile.nseg);
+        slot = slot == kBwdStages - 1 ? 0 : slot + 1;
+    }
+
+    // ---- epilogue: each wave lays its 32 rows of both gradients out row-major in a piece of the idle
+    // stages (pitch 144 bytes) and stores them 16 bytes per lane, eight lanes to a row
+    __syncthreads();           // every wave is done with the stages
+    constexpr int kPitch = kD * 2 + 16;
+    char* mine = reinterpret_cast<char*>(&t_lds[wave >> 1][0][0]) + (wave & 1) * (64 * kPitch);   // 2 x 32 rows
+    if (wave_live) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which)
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const floatx16& a = which == 0 ? dk_acc[db] : dv_acc[db];
+                    const bf16x4 o = {(__bf16)a[4 * vq], (__bf16)a[4 * vq + 1], (__bf16)a[4 * vq + 2], (__bf16)a[4 * vq + 3]};
+                    *reinterpret_cast<bf16x4*>(mine + (32 * which + j) * kPitch + (32 * db + 8 * vq + 4 * g) * 2) = o;
+                }
+        // the wave reads back only what it wrote itself; LDS operations of a wave complete in order
+        const int srow = lane >> 3, schunk = lane & 7;
+#pragma unroll
+        for (int which = 0; which < 2; ++which)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int row = 8 * s + srow, slot_r = wave * 32 + row;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(mine + (32 * which + row) * kPitch + 16 * schunk);
+                if (slot_r < tile.nrows) {
+                    const int64_t n = row_idx[slot_r];
+                    uint16_t* dst = (which == 0 ? grad_k : grad_v) + (out_bh + n * p.H) * kD;
+                    *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(dst) + 16 * schunk) = val;
+                }
+            }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_bwd_bf16(const BwdParams& p, int n_items, hipStream_t st) {
-    hipLaunchKernelGGL((bwd_bf16_kernel<0>), dim3(n_items), dim3(256), 0, st, p);
-    hipLaunchKernelGGL((bwd_bf16_kernel<1>), dim3(n_items), dim3(256), 0, st, p);
-    hipLaunchKernelGGL((bwd_bf16_kernel<2>), dim3(n_items), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(bwd_dq_bf16_kernel, dim3(n_items), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(bwd_dkdv_bf16_kernel, dim3(n_items), dim3(512), 0, st, p);
     return hipGetLastError();
 }
 
