@@ -113,7 +113,7 @@ def qkv(seed: int, B: int, N: int, H: int, D: int, dtype: str):
     return tuple(st), tuple(ex)
 
 
-# The workloads the benchmark spec lists, as (name -> parameters).  Head offset is
+# The workloads of the task definition, as (name -> parameters).  Head offset is
 # h mod r unless "offsets" is given.
 CONFIGS = {
     "tiny": dict(B=1, H=1, N=256, D=64, dtype="f32", branches=[(64, 2)], seed=BASE_SEED + 1),
