@@ -329,3 +329,28 @@ def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
     mx, _ = error_stats(to_f64(out_m), o_ref)
     check_lse(to_f64(lse_m), l_ref, atol=1e-5, rtol=1e-5)
     assert mx <= F32_MAX
+
+
+def test_bf16_tensors_beyond_two_gigabytes(B):
+    """344 images: every tensor passes 2^31 bytes, so any 32-bit byte or element offset in the kernels
+    or the plan would show.  The first, a middle and the last image must come out bit for bit as when they
+    are run on their own (each tile's arithmetic does not depend on the launch around it); the same for
+    the gradients."""
+    import torch
+    Bsz, N, H, D = 344, 4096, 12, 64
+    branches = [(1024, 1), (2048, 2), (4096, 4)]
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    q, k, v, g = (torch.randn((Bsz, N, H, D), device="cuda", dtype=torch.float32, generator=gen).bfloat16()
+                  for _ in range(4))
+    assert q.numel() * 2 > 2 ** 31
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125)
+    torch.cuda.synchronize()
+    for b in (0, 171, Bsz - 1):
+        sl = slice(b, b + 1)
+        o1, l1 = B.forward(q[sl], k[sl], v[sl], branches, 0.125)
+        assert bool((o1 == out[sl]).all()) and bool((l1 == lse[sl]).all()), b
+        g1 = B.backward(q[sl], k[sl], v[sl], o1, l1, g[sl].contiguous(), branches, 0.125)
+        for got, full in zip(g1, (dq, dk, dv)):
+            assert bool((got == full[sl]).all()), b
+    assert bool(torch.isfinite(out[-1].float()).all())
