@@ -181,3 +181,32 @@ def test_plan_keeps_a_unit_on_one_die_when_there_are_enough_units(B):
     assert all(len(d) == 1 for d in die_of.values())
     per_die = np.bincount([next(iter(d)) for d in die_of.values()], minlength=8)
     assert per_die.min() == per_die.max() == 24
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_plan_of_random_problems(B, seed):
+    """Random sizes, branch sets (also ragged ones) and offsets: every (h, n) in exactly one tile, and every
+    tile carries exactly the key lists the definition gives its rows."""
+    rng = np.random.default_rng(50 + seed)
+    Bsz, H, N, nb = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(1, 700)), int(rng.integers(1, 9))
+    branches, offs = [], []
+    for _ in range(nb):
+        r = int(rng.integers(1, 8))
+        branches.append((int(rng.integers(1, 2 * N + 1)), r))
+        offs.append([int(rng.integers(0, r)) for _ in range(H)])
+    offs = offs if seed % 2 else None
+    p = B.plan_describe(Bsz, H, N, branches, offs)
+    tiles, rows, segs, items = p["tiles"], p["rows"], p["segs"], p["items"]
+    seen = np.zeros((H, N), dtype=np.int32)
+    for (h, rb, nr, sb, ns, _) in tiles:
+        assert 1 <= nr <= 256 and ns <= nb
+        exp = _expected_key_sets(N, h, branches, offs)
+        got = [tuple(int(x) for x in segs[s]) for s in range(sb, sb + ns)]
+        for n in rows[rb:rb + nr]:
+            seen[h, n] += 1
+            assert got == exp[int(n)], (h, int(n))
+        for (first, stride, count) in got:
+            assert count >= 1 and 0 <= first and first + stride * (count - 1) < N
+    assert np.all(seen == 1)
+    real = items[items[:, 0] >= 0]
+    assert len(items) % 8 == 0 and len(set(map(tuple, real.tolist()))) == len(real) == len(tiles) * Bsz
