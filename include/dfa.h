@@ -36,7 +36,10 @@
  *     (tile lists in device memory, a few hundred KB each), keyed by device and problem
  *     shape.  The first call with a new shape allocates and uploads its plan
  *     (synchronously); later calls with that shape allocate nothing.
- *     dfa_release_plans() frees them.
+ *     dfa_release_plans() frees them.  A bf16 dfa_forward whose plan has fewer workgroups than the
+ *     chip has compute units (a single image, say) walks every tile with several workgroups and
+ *     merges their fp32 partial results; those live in the plan too (up to 4 x B*N*H*65 floats),
+ *     so two such calls with the same shape must not overlap on different streams.
  */
 #ifndef DFA_H
 #define DFA_H

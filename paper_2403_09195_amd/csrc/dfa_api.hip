@@ -25,7 +25,15 @@ struct DevicePlan {
     const Item* items = nullptr;
     int32_t n_items = 0;
     int device = 0;
+    // launches with few workgroups walk every tile with `split` workgroups (see launch_fwd_bf16_split);
+    // their fp32 partial results go here: out [split][B,N,H,D], then lse [split][B,H,N]
+    int32_t split = 1;
+    float* split_out = nullptr;
+    float* split_lse = nullptr;
 };
+
+constexpr int kChipWorkgroupSlots = 512;    // 256 CUs x 2 workgroups of the bf16 forward kernel
+constexpr int kMaxSplit = 4;
 
 std::mutex g_mu;
 std::map<std::vector<int32_t>, DevicePlan> g_plans;
@@ -61,7 +69,15 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     const size_t b_items = align256(hp.items.size() * sizeof(Item));
     DevicePlan dp;
     dp.device = device;
-    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items) != hipSuccess) return DFA_ERR_LAUNCH;
+    // fewer workgroups than CUs: the launch is as long as its longest tile's walk, so split the walks
+    size_t b_split = 0;
+    const int64_t rows_total = (int64_t)B * N * H;
+    if (hp.items.size() * 2 <= (size_t)kChipWorkgroupSlots) {
+        dp.split = std::min<int>(kMaxSplit, kChipWorkgroupSlots / (int)std::max<size_t>(hp.items.size(), 1));
+        if (dp.split >= 2) b_split = align256((size_t)dp.split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float));
+        else dp.split = 1;
+    }
+    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items + b_split) != hipSuccess) return DFA_ERR_LAUNCH;
     char* base = static_cast<char*>(dp.base);
     bool ok = true;
     ok = ok && hipMemcpy(base, hp.tiles.data(), hp.tiles.size() * sizeof(Tile), hipMemcpyHostToDevice) == hipSuccess;
@@ -78,6 +94,10 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     dp.segs = reinterpret_cast<const KeySeg*>(base + b_tiles + b_rows);
     dp.items = reinterpret_cast<const Item*>(base + b_tiles + b_rows + b_segs);
     dp.n_items = (int32_t)hp.items.size();
+    if (dp.split >= 2) {
+        dp.split_out = reinterpret_cast<float*>(base + b_tiles + b_rows + b_segs + b_items);
+        dp.split_lse = dp.split_out + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
+    }
     g_plans[key] = dp;
     *out = dp;
     return DFA_OK;
@@ -147,10 +167,20 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     p.out = out; p.lse = lse;
     p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
     p.H = H; p.N = N; p.scale = scale;
+    p.split = 1; p.part_rows = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (dt == DFA_BF16) e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
-    else e = launch_fwd_f32(p, dp.n_items, st);        // fp32 inputs always give fp32 output
+    if (dt == DFA_BF16 && !out_f32 && dp.split >= 2) {
+        // few workgroups: partial results per share of the key walk, then their log-sum-exp merge
+        p.out = dp.split_out; p.lse = dp.split_lse;
+        p.split = dp.split; p.part_rows = (int64_t)B * N * H;
+        e = launch_fwd_bf16_split(p, dp.n_items, st);
+        if (e == hipSuccess) e = launch_merge(dp.split_out, dp.split_lse, dp.split, B, H, N, true, out, lse, st);
+    } else if (dt == DFA_BF16) {
+        e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
+    } else {
+        e = launch_fwd_f32(p, dp.n_items, st);         // fp32 inputs always give fp32 output
+    }
     return e == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
 }
 

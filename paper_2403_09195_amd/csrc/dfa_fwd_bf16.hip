@@ -265,7 +265,8 @@ __device__ __forceinline__ void store4<__bf16>(__bf16* dst, float a, float b, fl
     *reinterpret_cast<bf16x4*>(dst) = o;
 }
 
-template <typename OutT>
+// kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split).
+template <typename OutT, bool kSplit>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void dfa_fwd_bf16_kernel(const FwdParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t k_lds[kStages][kStageElems];
@@ -273,7 +274,8 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     __shared__ int32_t row_idx[kTileRows];
     __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
 
-    const Item item = p.items[blockIdx.x];
+    const int part = kSplit ? (int)(blockIdx.x % (unsigned)p.split) : 0;
+    const Item item = p.items[kSplit ? blockIdx.x / (unsigned)p.split : blockIdx.x];
     if (item.tile < 0) return;
     const Tile tile = p.tiles[item.tile];
     const int tid = threadIdx.x;
@@ -284,7 +286,8 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     if (tid < tile.nseg) seg_lds[tid] = p.segs[tile.seg_begin + tid];
     __syncthreads();
 
-    OutT* const out = static_cast<OutT*>(p.out);
+    OutT* const out = static_cast<OutT*>(p.out) + (kSplit ? part * p.part_rows * kD : 0);
+    float* const lse_out = kSplit ? p.lse + part * p.part_rows : p.lse;
     const int64_t out_bh = (int64_t)b * p.N * p.H + h;   // in rows; row n adds n * H
 
     if (tile.nseg == 0) {
@@ -295,8 +298,8 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             char* dst = reinterpret_cast<char*>(out + (out_bh + (int64_t)row_idx[rr] * p.H) * kD) + 16 * ch;
             *reinterpret_cast<u32x4*>(dst) = u32x4{0u, 0u, 0u, 0u};
         }
-        if (p.lse && tid < tile.nrows)
-            p.lse[((int64_t)b * p.H + h) * p.N + row_idx[tid]] = -INFINITY;
+        if (lse_out && tid < tile.nrows)
+            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[tid]] = -INFINITY;
         return;
     }
 
@@ -333,10 +336,27 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     const uint32_t v_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &v_lds[0][0]);
     constexpr uint32_t kStageBytes = kStageElems * 2;
 
-    // stage 0 on its way before anything else
     KeyCursor pf;
     pf.s = 0;
     pf.t = 0;
+    if (kSplit) {
+        // this workgroup's share of the steps: [first, last) of the tile's n_steps
+        const int first = part * n_steps / p.split, last = (part + 1) * n_steps / p.split;
+        n_steps = last - first;
+        if (n_steps == 0) {        // a tile with fewer steps than parts: this part has no keys
+            if (tid < tile.nrows) lse_out[((int64_t)b * p.H + h) * p.N + row_idx[tid]] = -INFINITY;
+            return;
+        }
+        int skip = first;
+        for (;;) {                 // ends: first < the tile's step count
+            const int in_seg = (__builtin_amdgcn_readfirstlane(seg_lds[pf.s].count) + kKeyTile - 1) / kKeyTile;
+            if (skip < in_seg) break;
+            skip -= in_seg;
+            ++pf.s;
+        }
+        pf.t = skip;
+    }
+    // stage 0 on its way before anything else
     cursor_load(pf, seg_lds);
     KeyCursor cur = pf;
     issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr, v_lds_addr);
@@ -451,8 +471,8 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const int slot = wave * 64 + qb * 32 + j_e;
         const float l_tot = wave_half_sum(l_run[qb]);
         inv[qb] = 1.0f / l_tot;
-        if (p.lse && g_e == 0 && slot < tile.nrows)
-            p.lse[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        if (lse_out && g_e == 0 && slot < tile.nrows)
+            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
     if constexpr (sizeof(OutT) == 2) {
         // bf16 rows are 128 bytes.  A lane holds 4 consecutive d of one row per register quad; written
@@ -508,9 +528,17 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st) {
     if (out_f32)
-        hipLaunchKernelGGL(dfa_fwd_bf16_kernel<float>, dim3(n_items), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, false>), dim3(n_items), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(dfa_fwd_bf16_kernel<__bf16>, dim3(n_items), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, false>), dim3(n_items), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// Launches with fewer workgroups than the chip has CUs are bound by the longest tile's walk, not by
+// throughput: here every tile is walked by p.split workgroups, each over a share of its steps,
+// into fp32 partial results (p.out, p.lse: [split][...]) that the caller merges by their lse.
+hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_items, hipStream_t st) {
+    hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true>), dim3(n_items * p.split), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
