@@ -210,3 +210,10 @@ def test_plan_of_random_problems(B, seed):
     assert np.all(seen == 1)
     real = items[items[:, 0] >= 0]
     assert len(items) % 8 == 0 and len(set(map(tuple, real.tolist()))) == len(real) == len(tiles) * Bsz
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)

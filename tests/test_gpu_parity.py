@@ -355,3 +355,9 @@ def test_bf16_tensors_beyond_two_gigabytes(B):
         for got, full in zip(g1, (dq, dk, dv)):
             assert bool((got == full[sl]).all()), b
     assert bool(torch.isfinite(out[-1].float()).all())
+
+
+def test_mfma_only_loop_reports_a_plausible_ceiling(B):
+    for random_operands in (False, True):
+        tflops, mhz = B.mfma_peak(random_operands)
+        assert 800.0 < tflops < 2600.0 and 1000.0 < mhz < 2600.0, (tflops, mhz)
