@@ -77,7 +77,10 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
         if (dp.split >= 2) b_split = align256((size_t)dp.split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float));
         else dp.split = 1;
     }
-    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items + b_split) != hipSuccess) return DFA_ERR_LAUNCH;
+    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items + b_split) != hipSuccess) {
+        (void)hipGetLastError();   // reported here; a later launch's check must not see it again
+        return DFA_ERR_LAUNCH;
+    }
     char* base = static_cast<char*>(dp.base);
     bool ok = true;
     ok = ok && hipMemcpy(base, hp.tiles.data(), hp.tiles.size() * sizeof(Tile), hipMemcpyHostToDevice) == hipSuccess;
@@ -98,7 +101,12 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
         dp.split_out = reinterpret_cast<float*>(base + b_tiles + b_rows + b_segs + b_items);
         dp.split_lse = dp.split_out + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
     }
-    g_plans[key] = dp;
+    try {
+        g_plans[key] = dp;
+    } catch (const std::bad_alloc&) {
+        (void)hipFree(dp.base);
+        throw;
+    }
     *out = dp;
     return DFA_OK;
 }

@@ -112,6 +112,31 @@ def test_backward_bf16_sam_scale_config(B, oracle):
         assert mx <= 3e-2 and mean <= 2e-3
 
 
+def test_backward_bf16_full_size_on_sampled_images(B, oracle):
+    """The launch the backward benchmark times (16 images, 12 heads, 4096 tokens): every gradient is
+    finite, and three sampled (image, head) pairs are checked in full against the oracle, each as a
+    one-head problem whose explicit offsets are that head's."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["throughput"]
+    (q, k, v), ex = make_qkv(c["seed"], c["B"], c["N"], c["H"], c["D"], "bf16")
+    g, ge = _dout(c["seed"], (c["B"], c["N"], c["H"], c["D"]), "bf16")
+    out, lse = B.forward(q, k, v, c["branches"], 0.125)
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, c["branches"], 0.125)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert bool(torch.isfinite(t.float()).all())
+    rng = np.random.default_rng(c["seed"] + 1)
+    for _ in range(3):
+        b, h = int(rng.integers(0, c["B"])), int(rng.integers(0, c["H"]))
+        one = [np.ascontiguousarray(x[b:b + 1, :, h:h + 1]) for x in (*ex, ge)]
+        offs = [[h % r] for _, r in c["branches"]]
+        refs = oracle.backward(*one, c["branches"], 0.125, head_offsets=offs)
+        for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+            mx, mean = _report(f"throughput b={b} h={h} {name}", to_f64(got[b:b + 1, :, h:h + 1]), ref)
+            assert mx <= 3e-2 and mean <= 2e-3
+
+
 @pytest.mark.parametrize("count", [1, 31, 33, 64, 65, 129])
 def test_backward_bf16_list_lengths_around_the_block_sizes(B, oracle, count):
     """Lists of `count` rows: one row (P = 1, dq = dk = 0, dv = dout), and lengths just below, at and
