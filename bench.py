@@ -213,6 +213,9 @@ def main():
                          "dilated attention against dense attention in the same kernel (w = N, r = 1)")
     ap.add_argument("--backward", action="store_true",
                     help="time dfa_backward (dq, dk, dv) on --workload")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="diagnostic: the default line or --backward on all-zero tensors of the same shape (same work, "
+                         "no operand bit flips): the gap to the synthetic-data time shows how far the launch is power-limited")
     ap.add_argument("--layers", type=int, default=12, help="--stack: number of layers")
     ap.add_argument("--heads", type=int, default=12, help="--stack: heads of 64 (embed = 64 * heads)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -256,6 +259,8 @@ def main():
     Bsz, H, N, D, branches = cfg["B"], cfg["H"], cfg["N"], cfg["D"], cfg["branches"]
     scale = 1.0 / (D ** 0.5)
     storage, exact = synth.qkv(cfg["seed"], Bsz, N, H, D, cfg["dtype"])
+    if args.zero_inputs:
+        storage, exact = tuple(np.zeros_like(a) for a in storage), tuple(np.zeros_like(a) for a in exact)
 
     def dev(a):
         if a.dtype == np.uint16:
@@ -276,8 +281,11 @@ def main():
         g = torch.from_numpy(synth.tensor(cfg["seed"], 7, (Bsz, N, H, D), cfg["dtype"])[0]
                              .view(np.int16 if cfg["dtype"] == "bf16" else np.float32)).cuda()
         g = g.view(torch.bfloat16) if cfg["dtype"] == "bf16" else g
-        steps = max(1, min(args.steps, 5))
-        binding.backward(q, k, v, out, lse, g, branches, scale)
+        if args.zero_inputs:
+            g.zero_()
+        steps = max(1, args.steps if cfg["dtype"] == "bf16" else min(args.steps, 20))   # the fp32 path takes tens of ms
+        for _ in range(max(1, min(args.warmup, steps))):
+            binding.backward(q, k, v, out, lse, g, branches, scale)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -293,7 +301,7 @@ def main():
         peak = MFMA_BF16_PEAK_TFLOPS if mfma else 157.3
         print(json.dumps({"metric": "dfa_backward ms per step (dq, dk, dv)", "value": ms, "unit": "ms", "steps": steps,
                           "higher_is_better": False, "config": {"workload": args.workload},
-                          "dtype": "bf16" if mfma else "f32",
+                          "dtype": "bf16" if mfma else "f32", "data": "zeros" if args.zero_inputs else "synthetic",
                           "useful_backward_TFLOP/s": 2.5 * flops / ms / 1e9,
                           "roofline": {"bound": "mfma" if mfma else "alu", "achieved": executed / ms / 1e9, "peak": peak,
                                        "unit": "TFLOP/s", "frac": executed / ms / 1e9 / peak,
@@ -347,7 +355,7 @@ def main():
     # the second half of the headline metric: one 1024^2 image through all 12 layers of the encoder
     # attention stack (projections included), from a short run of the stack workload
     stack = None
-    if args.workload == WORKLOAD:
+    if args.workload == WORKLOAD and not args.zero_inputs:
         try:
             del q, k, v, out, lse
             rep = stack_report(binding, synth, torch, np, 5, 2, False)
@@ -360,7 +368,8 @@ def main():
         "metric": "dilated-attention TFLOP/s (useful attention FLOPs, 4*D per kept query-key pair)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+        "data": "zeros (power diagnostic, not the benchmark)" if args.zero_inputs else "synthetic",
         "config": {"workload": f"{args.workload}: B={Bsz} H={H} N={N} D={D} branches={branches} offset=h mod r scale=1/sqrt(D)"},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "mfma_only_loop": {"constant_operands": {"TFLOP/s": peak_const, "shader_MHz": mhz_const},
