@@ -174,12 +174,16 @@ int dfa_scatter(const void *og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
 /*
  * Host-side view of the launch plan dfa_forward would use (no GPU needed): the query
  * rows of each head are grouped by the set of (branch, segment) pairs that keep them and
- * cut into tiles; every tile carries one arithmetic key progression per member branch.
+ * cut into tiles; every tile carries its keys as arithmetic progressions: one per member
+ * branch, or, where the member branches keep some keys more than once, the multiset union of
+ * those cut into progressions of one multiplicity each (a key kept by m branches is visited
+ * once and its softmax weight multiplied by m: the same sum as m visits, section 3.1's merge
+ * being a softmax over the multiset union of the branches' keys).
  * Pass NULL arrays to query the sizes only.
  *   n_tiles, n_rows, n_segs, n_items   out, host: entry counts
  *   tiles  host int32 [n_tiles][6] = (h, row_begin, nrows, seg_begin, nseg, unused)
  *   rows   host int32 [n_rows]     token positions, tile after tile
- *   segs   host int32 [n_segs][3]  = (first key, key stride, key count)
+ *   segs   host int32 [n_segs][4]  = (first key, key stride, key count, multiplicity)
  *   items  host int32 [n_items][2] = (tile or -1 for padding, b) in launch order
  */
 int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branches, int32_t nb,

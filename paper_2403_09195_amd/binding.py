@@ -347,7 +347,7 @@ def plan_describe(B, H, N, branches, head_offsets=None):
     nt, nr, ns, ni = (c.value for c in cnt)
     tiles = np.zeros((nt, 6), dtype=np.int32)
     rows = np.zeros((nr,), dtype=np.int32)
-    segs = np.zeros((max(ns, 1), 3), dtype=np.int32)
+    segs = np.zeros((max(ns, 1), 4), dtype=np.int32)
     items = np.zeros((ni, 2), dtype=np.int32)
     p = lambda a: a.ctypes.data_as(_i32p)
     _check(lib().dfa_plan_describe(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(items)),

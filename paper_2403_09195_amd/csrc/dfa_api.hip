@@ -132,6 +132,14 @@ int check_stage_grid(int32_t B, int32_t H, int32_t N) {
     return DFA_OK;
 }
 
+// Largest stride a key progression of the plan can have: a branch's dilation rate, or, for keys that
+// several branches share, a divisor of the rates' common period (at most kMaxCoalesceLcm).
+int64_t max_key_stride(const dfa_branch_t* br, int32_t nb) {
+    int64_t s = nb > 1 ? kMaxCoalesceLcm : 1;
+    for (int x = 0; x < nb; ++x) s = std::max<int64_t>(s, br[x].r);
+    return s;
+}
+
 int make_offsets(const int32_t* head_offsets, int32_t H, int32_t r, HeadOffsets* o) {
     std::memset(o, 0, sizeof(*o));
     if (!head_offsets) return DFA_OK;
@@ -159,10 +167,8 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     if (reinterpret_cast<uintptr_t>(out) % 16 || (lse && reinterpret_cast<uintptr_t>(lse) % 4)) return DFA_ERR_ALIGN;
 
     // the copy lanes address a 64-key step with 32-bit byte offsets from its first row
-    for (int x = 0; x < nb; ++x) {
-        const int64_t pitch = (int64_t)branches[x].r * (sk.n > sv.n ? sk.n : sv.n) * es;
-        if (sk.n <= 0 || sv.n <= 0 || sq.n <= 0 || 64 * pitch + 128 >= ((int64_t)1 << 31)) return DFA_ERR_TOO_LARGE;
-    }
+    if (sk.n <= 0 || sv.n <= 0 || sq.n <= 0) return DFA_ERR_TOO_LARGE;
+    if (64 * max_key_stride(branches, nb) * std::max(sk.n, sv.n) * es + 128 >= ((int64_t)1 << 31)) return DFA_ERR_TOO_LARGE;
     DevicePlan dp;
     rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
     if (rc != DFA_OK) return rc;
@@ -326,9 +332,9 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
     rc = check_stage_grid(B, H, N);          // the per-row preparation carries b on the grid
     if (rc != DFA_OK) return rc;
     // the copy lanes address a 64-row step with 32-bit byte offsets from its first row
-    for (int x = 0; x < nb; ++x) {
+    {
         const int64_t widest = std::max(std::max(sq.n, sk.n), std::max(sv.n, (int64_t)H * D));
-        if (sq.n <= 0 || sk.n <= 0 || sv.n <= 0 || 64 * (int64_t)branches[x].r * widest * es + 128 >= ((int64_t)1 << 31))
+        if (sq.n <= 0 || sk.n <= 0 || sv.n <= 0 || 64 * max_key_stride(branches, nb) * widest * es + 128 >= ((int64_t)1 << 31))
             return DFA_ERR_TOO_LARGE;
     }
     try {
@@ -419,9 +425,10 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
         if (rows) std::memcpy(rows, hp.rows.data(), hp.rows.size() * sizeof(int32_t));
         if (segs)
             for (size_t s = 0; s < hp.segs.size(); ++s) {
-                segs[3 * s] = hp.segs[s].key0;
-                segs[3 * s + 1] = hp.segs[s].stride;
-                segs[3 * s + 2] = hp.segs[s].count;
+                segs[4 * s] = hp.segs[s].key0;
+                segs[4 * s + 1] = hp.segs[s].stride;
+                segs[4 * s + 2] = hp.segs[s].count;
+                segs[4 * s + 3] = hp.seg_mult[s];
             }
         if (items)
             for (size_t i = 0; i < hp.items.size(); ++i) {

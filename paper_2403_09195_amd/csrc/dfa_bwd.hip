@@ -5,7 +5,9 @@
 // lse of the forward pass, P(n, j) = exp(scale q_n.k_j - lse_n) per (branch, n, j) pair and
 // delta_n = dout_n . out_n:
 //   dv_j += P dout_n,   ds = P (dout_n . v_j - delta_n),   dq_n += scale ds k_j,   dk_j += scale ds q_n.
-// P is recomputed from lse, nothing of the forward pass is stored besides out and lse.
+// P is recomputed from lse, nothing of the forward pass is stored besides out and lse.  Where the
+// plan visits a pair once for the m branches that hold it, P carries the factor m (every formula
+// above is linear in P).
 //
 // This file: the per-row preparation both precisions share (delta, and lse in base-2 units) and
 // the fp32 path, correctness-first kernels in fp32 vector arithmetic on the same launch plan as
@@ -188,11 +190,11 @@ void bwd_kernel(const BwdParams p) {
                 const float* br = b_lds + c * kD;
                 const float sc = dot_row(x0, ar) * p.scale;                       // scale q.k
                 if (kMode == 0) {
-                    const float pr = __builtin_amdgcn_exp2f(sc * kLog2e - my_l);
+                    const float pr = __builtin_amdgcn_exp2f(sc * kLog2e + seg.log2_mult - my_l);
                     const float ds = pr * (dot_row(x1, br) - my_d) * p.scale;
                     axpy_row(ds, ar, acc);                                        // dq += scale ds k
                 } else {
-                    const float pr = __builtin_amdgcn_exp2f(sc * kLog2e - l_lds[c]);
+                    const float pr = __builtin_amdgcn_exp2f(sc * kLog2e + seg.log2_mult - l_lds[c]);
                     if (kMode == 1) {
                         axpy_row(pr, br, acc);                                    // dv += P dout
                     } else {

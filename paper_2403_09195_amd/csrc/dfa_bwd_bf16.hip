@@ -98,6 +98,28 @@ __device__ __forceinline__ void pack_block(const float (&x)[16], u32x4 (&pb)[2])
     }
 }
 
+// P and dS of one 32 x 32 block of the dk/dv kernel.  lp / dl: lse (base-2 units) and delta of the walked
+// queries in LDS; register v of a lane is block position 16*(v/8) + 8*g + v%8, lp and dl point at
+// position 8*g.  kBias: the pairs of this step count m times, log2 m = bias (see KeySeg).
+template <bool kBias>
+__device__ __forceinline__ void probs_block(const floatx16& s, const floatx16& dp, const float* lp, const float* dl,
+                                            float c, float scale, float bias, float (&pr)[16], float (&ds)[16]) {
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int e = 0; e < 8; e += 4) {
+            const float4 l2 = *reinterpret_cast<const float4*>(lp + 16 * hf + e);
+            const float4 dd = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
+            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dda[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int v = 8 * hf + e + x;
+                pr[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, kBias ? bias - l2a[x] : -l2a[x]));
+                ds[v] = pr[v] * (dp[v] - dda[x]) * scale;
+            }
+        }
+}
+
 // dq of a tile: its rows are queries, the lists are walked as keys (K in "A" and "T" layout, V in "A"
 // layout).  Four waves of 64 rows each.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -106,7 +128,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
     constexpr int kCopies = 2 * kTensors;                            // per wave per stage
     __shared__ __attribute__((aligned(1024))) uint16_t t_lds[kTensors][kBwdStages][kStageElems];
     __shared__ int32_t row_idx[kTileRows];
-    __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
+    __shared__ KeySeg seg_lds[kMaxTileSegs];
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
@@ -219,8 +241,16 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
 
+    // pairs that count m times (see KeySeg): P carries the factor m, i.e. log2 m is taken off the row's
+    // lse while the walk is inside such a progression
+    float bias_cur = 0.f;
     int slot = 0;
     for (int i = 0; i < n_steps; ++i) {
+        if (cur.bias != bias_cur) {
+            my_l2[0] -= cur.bias - bias_cur;
+            my_l2[1] -= cur.bias - bias_cur;
+            bias_cur = cur.bias;
+        }
         // stage i has landed once at most the copies of stage i+1 are still outstanding (the loads of
         // the own rows were issued after the first two stages, so the first wait covers them)
         if (i == 0 || i + 1 >= n_steps) wait_vmcnt<0>(); else wait_vmcnt<kCopies>();
@@ -315,7 +345,7 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t t_lds[kTensors][kBwdStages][kStageElems];
     __shared__ __attribute__((aligned(256))) float sc_lds[2][kBwdStages][kKeyTile];
     __shared__ int32_t row_idx[kTileRows];
-    __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
+    __shared__ KeySeg seg_lds[kMaxTileSegs];
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
@@ -454,20 +484,8 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
                 {
                     const float* lp = &sc_lds[0][slot][32 * ws + 8 * g];
                     const float* dl = &sc_lds[1][slot][32 * ws + 8 * g];
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                        for (int e = 0; e < 8; e += 4) {
-                            const float4 l2 = *reinterpret_cast<const float4*>(lp + 16 * hf + e);
-                            const float4 dd = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
-                            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dda[4] = {dd.x, dd.y, dd.z, dd.w};
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) {
-                                const int v = 8 * hf + e + x;
-                                pr[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, -l2a[x]));
-                                ds[v] = pr[v] * (dp[v] - dda[x]) * scale;
-                            }
-                        }
+                    if (cur.bias == 0.f) probs_block<false>(s, dp, lp, dl, c, scale, 0.f, pr, ds);
+                    else probs_block<true>(s, dp, lp, dl, c, scale, cur.bias, pr, ds);
                 }
                 u32x4 pp[2], ps[2];
                 pack_block(pr, pp);

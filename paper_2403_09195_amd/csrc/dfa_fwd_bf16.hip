@@ -2,7 +2,8 @@
 //
 // One workgroup (4 waves) owns a tile of up to 256 query rows that share the same key lists
 // (section 3.1: all of them are kept by the same branches and fall into the same segment of
-// each).  It walks the key lists of its member branches one after the other, carrying ONE
+// each).  It walks the key lists of its member branches one after the other (keys that several of
+// them keep are visited once and weighted by their multiplicity, see KeySeg), carrying ONE
 // online-softmax state (reference exponent, running sum, accumulator) per query row across all
 // of them: continuing the softmax over the next branch's keys is the log-sum-exp merge of the
 // branches, so no partial result ever leaves the registers.
@@ -272,7 +273,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t k_lds[kStages][kStageElems];
     __shared__ __attribute__((aligned(1024))) uint16_t v_lds[kStages][kStageElems];
     __shared__ int32_t row_idx[kTileRows];
-    __shared__ KeySeg seg_lds[DFA_MAX_BRANCHES];
+    __shared__ KeySeg seg_lds[kMaxTileSegs];
 
     const int part = kSplit ? (int)(blockIdx.x % (unsigned)p.split) : 0;
     const Item item = p.items[kSplit ? blockIdx.x / (unsigned)p.split : blockIdx.x];
@@ -406,8 +407,12 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // maximum: it is only moved (to the exact maximum seen so far) when a block's sums show
     // that exponents got large, so that the common case needs no row maximum at all.  Between
     // moves every p stays below kRebaseThreshold, which fp32 and bf16 carry without loss.
+    // A progression whose keys count m times adds log2(m) to its scaled scores.  That is done by holding
+    // m_ref as (reference exponent - log2 m of the progression being walked) and moving it when the
+    // walk enters a progression of another multiplicity; sums and accumulator stay on the true reference.
     float m_ref[2] = {-INFINITY, -INFINITY};
     float l_run[2] = {0.f, 0.f};               // this lane's share of the running sum
+    float bias_cur = 0.f;                      // log2 m held in m_ref (wave-uniform)
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
 
@@ -424,6 +429,11 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     int stage = 0;
     for (int s = 0; s < n_steps; ++s) {
         const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+        if (cur.bias != bias_cur) {            // both blocks of this step still hold raw scores
+            m_ref[0] -= cur.bias - bias_cur;
+            m_ref[1] -= cur.bias - bias_cur;
+            bias_cur = cur.bias;
+        }
         const int stage_prev = stage == 0 ? kStages - 1 : stage - 1;
         const int stage_next = stage == kStages - 1 ? 0 : stage + 1;
         float psum[2];
@@ -472,7 +482,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const float l_tot = wave_half_sum(l_run[qb]);
         inv[qb] = 1.0f / l_tot;
         if (lse_out && g_e == 0 && slot < tile.nrows)
-            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
     if constexpr (sizeof(OutT) == 2) {
         // bf16 rows are 128 bytes.  A lane holds 4 consecutive d of one row per register quad; written

@@ -56,6 +56,7 @@ void dfa_fwd_f32_kernel(const FwdParams p) {
 
     for (int s = 0; s < tile.nseg; ++s) {
         const KeySeg seg = p.segs[tile.seg_begin + s];
+        const float ln_mult = seg.log2_mult * kLn2;   // a key that counts m times: weight m exp(s) = exp(s + ln m)
         for (int t = 0; t * kKeyTile < seg.count; ++t) {
             __syncthreads();               // previous tile fully consumed
             // thread -> (key tid/16 + 16u, 16-byte chunk tid%16)
@@ -89,7 +90,7 @@ void dfa_fwd_f32_kernel(const FwdParams p) {
                         d3 = fmaf(qv[d + 3], x.w, d3);
                     }
                     const float dot = (d0 + d1) + (d2 + d3);
-                    sc[jj] = (c0 + jj < nvalid) ? dot * p.scale : -INFINITY;
+                    sc[jj] = (c0 + jj < nvalid) ? dot * p.scale + ln_mult : -INFINITY;
                     mx = fmaxf(mx, sc[jj]);
                 }
                 const float m_new = fmaxf(m_run, mx);

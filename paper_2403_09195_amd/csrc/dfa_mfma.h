@@ -49,17 +49,19 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
 
-// Walks the 64-key steps of a tile's key lists: segment after segment (one per member branch).
+// Walks the 64-key steps of a tile's key list, progression after progression.
 // All fields are wave-uniform and kept in scalar registers.
 struct KeyCursor {
-    int s, t;                  // segment index within the tile, 64-key step within the segment
-    int key0, stride, count;   // the segment: kept keys are key0 + stride * j, j < count
+    int s, t;                  // progression index within the tile, 64-key step within the progression
+    int key0, stride, count;   // the progression: keys key0 + stride * j, j < count
+    float bias;                // log2 of the multiplicity of its keys, added to the base-2 scaled score
 };
 
 __device__ __forceinline__ void cursor_load(KeyCursor& c, const KeySeg* seg_lds) {
     c.key0 = __builtin_amdgcn_readfirstlane(seg_lds[c.s].key0);
     c.stride = __builtin_amdgcn_readfirstlane(seg_lds[c.s].stride);
     c.count = __builtin_amdgcn_readfirstlane(seg_lds[c.s].count);
+    c.bias = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seg_lds[c.s].log2_mult)));
 }
 
 __device__ __forceinline__ void cursor_next(KeyCursor& c, const KeySeg* seg_lds, int nseg) {

@@ -1,10 +1,102 @@
 #include "dfa_plan.h"
 
 #include <algorithm>
+#include <cmath>
 #include <map>
 #include <numeric>
 
 namespace dfa {
+
+namespace {
+
+int64_t steps_of(const std::vector<KeySeg>& segs) {
+    int64_t n = 0;
+    for (const KeySeg& s : segs) n += (s.count + 63) / 64;
+    return n;
+}
+
+// The multiset union of the progressions in `plain` (one per member branch of a tile) rewritten
+// as progressions in which every key has one multiplicity.  With L the least common multiple of
+// the strides, a residue class mod L is either inside or outside each progression's own class,
+// so along one class the multiplicity only changes where a progression starts or ends.  Classes
+// covered by the same progressions are joined into coarser strides where they line up.
+// Returns false (outputs untouched) when L is too large, the list would not fit a tile, or no
+// 64-key step would be saved.
+bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::vector<int32_t>* out_mult) {
+    const int ns = (int)plain.size();
+    if (ns < 2) return false;
+    int64_t L = 1;
+    for (const KeySeg& s : plain) {
+        L = std::lcm<int64_t>(L, s.stride);
+        if (L > kMaxCoalesceLcm) return false;
+    }
+    std::vector<int64_t> last(ns);
+    for (int x = 0; x < ns; ++x) last[x] = plain[x].key0 + (int64_t)(plain[x].count - 1) * plain[x].stride;
+
+    std::vector<uint32_t> mask_of(L, 0);
+    for (int64_t rho = 0; rho < L; ++rho)
+        for (int x = 0; x < ns; ++x)
+            if ((rho - plain[x].key0) % plain[x].stride == 0) mask_of[rho] |= 1u << x;
+
+    std::vector<KeySeg> segs;
+    std::vector<int32_t> mult;
+    std::vector<char> used(L, 0);
+    for (int64_t rho0 = 0; rho0 < L; ++rho0) {
+        const uint32_t mask = mask_of[rho0];
+        if (used[rho0] || mask == 0) continue;
+        // where the multiplicity can change along these classes
+        std::vector<int64_t> cuts;
+        for (int x = 0; x < ns; ++x)
+            if (mask >> x & 1) {
+                cuts.push_back(plain[x].key0);
+                cuts.push_back(last[x] + 1);
+            }
+        std::sort(cuts.begin(), cuts.end());
+        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+        // the classes with this mask, as progressions (a mod g), smallest stride first
+        for (int64_t g = 1; g <= L; ++g) {
+            if (L % g) continue;
+            for (int64_t a = 0; a < g; ++a) {
+                bool all = true;
+                for (int64_t rho = a; rho < L && all; rho += g) all = !used[rho] && mask_of[rho] == mask;
+                if (!all) continue;
+                for (int64_t rho = a; rho < L; rho += g) used[rho] = 1;
+                size_t open = segs.size();                      // pieces of this (a mod g) start here
+                for (size_t c = 0; c + 1 < cuts.size(); ++c) {
+                    const int64_t lo = cuts[c], hi = cuts[c + 1];
+                    int32_t m = 0;
+                    for (int x = 0; x < ns; ++x)
+                        if ((mask >> x & 1) && plain[x].key0 <= lo && hi - 1 <= last[x]) ++m;
+                    if (m == 0) continue;
+                    const int64_t key0 = lo + (((a - lo) % g) + g) % g;
+                    if (key0 >= hi) continue;
+                    const int32_t count = (int32_t)((hi - 1 - key0) / g + 1);
+                    if (segs.size() > open && mult.back() == m &&
+                        segs.back().key0 + (int64_t)segs.back().count * g == key0) {
+                        segs.back().count += count;             // the progression runs on with the same multiplicity
+                    } else {
+                        segs.push_back(KeySeg{(int32_t)key0, (int32_t)g, count, std::log2((float)m)});
+                        mult.push_back(m);
+                    }
+                }
+            }
+        }
+    }
+    if ((int)segs.size() > kMaxTileSegs || steps_of(segs) >= steps_of(plain)) return false;
+    // ascending first keys: consecutive steps then read neighbouring rows
+    std::vector<size_t> order(segs.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](size_t i, size_t j) { return segs[i].key0 < segs[j].key0; });
+    out->clear();
+    out_mult->clear();
+    for (size_t i : order) {
+        out->push_back(segs[i]);
+        out_mult->push_back(mult[i]);
+    }
+    return true;
+}
+
+}  // namespace
 
 int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets) {
     if (nb < 1 || nb > DFA_MAX_BRANCHES) return DFA_ERR_BRANCHES;
@@ -27,6 +119,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
     plan->tiles.clear();
     plan->rows.clear();
     plan->segs.clear();
+    plan->seg_mult.clear();
     plan->items.clear();
 
     std::vector<int64_t> tile_cost;   // (query, key) pairs of each tile
@@ -46,8 +139,8 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             const std::vector<int32_t>& s = g.first;
             const std::vector<int32_t>& rows = g.second;
             const int32_t seg_begin = (int32_t)plan->segs.size();
-            int32_t nseg = 0;
-            int64_t keys = 0;
+            std::vector<KeySeg> list;
+            std::vector<int32_t> list_mult;
             for (int x = 0; x < nb; ++x) {
                 if (s[x] < 0) continue;
                 const int32_t o = head_offset(offsets, H, x, h, br[x].r);
@@ -56,10 +149,23 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 const int64_t first = (int64_t)s[x] * br[x].w + o;
                 const int64_t end = std::min<int64_t>((int64_t)(s[x] + 1) * br[x].w, N);
                 const int32_t count = (int32_t)((end - 1 - first) / br[x].r + 1);   // >= 1: a row of the part is kept
-                plan->segs.push_back(KeySeg{(int32_t)first, br[x].r, count, 0});
-                keys += count;
-                ++nseg;
+                list.push_back(KeySeg{(int32_t)first, br[x].r, count, 0.f});
+                list_mult.push_back(1);
             }
+            // keys that several member branches keep are visited once, weighted by how many keep them
+            {
+                std::vector<KeySeg> merged;
+                std::vector<int32_t> merged_mult;
+                if (coalesce(list, &merged, &merged_mult)) {
+                    list.swap(merged);
+                    list_mult.swap(merged_mult);
+                }
+            }
+            const int32_t nseg = (int32_t)list.size();
+            int64_t keys = 0;
+            for (const KeySeg& sg : list) keys += sg.count;
+            plan->segs.insert(plan->segs.end(), list.begin(), list.end());
+            plan->seg_mult.insert(plan->seg_mult.end(), list_mult.begin(), list_mult.end());
             for (size_t lo = 0; lo < rows.size(); lo += kTileRows) {
                 const int32_t cnt = (int32_t)std::min<size_t>(kTileRows, rows.size() - lo);
                 Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, 0};

@@ -14,9 +14,17 @@ namespace dfa {
 
 constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
 constexpr int kNumXcd = 8;       // MI355X: 8 accelerator dies, workgroups dealt round-robin
+constexpr int kMaxTileSegs = 32; // key progressions per tile (the kernels hold a tile's list in LDS)
+constexpr int kMaxCoalesceLcm = 64;   // largest common period of a tile's dilation rates that is coalesced
 
-struct KeySeg {      // kept keys of one segment of one branch: key0 + stride * j, j < count
-    int32_t key0, stride, count, pad;
+// One arithmetic progression of a tile's key list: keys key0 + stride * j, j < count.  Either the
+// kept keys of one segment of one branch (multiplicity 1), or, where the member branches of a
+// tile keep some keys more than once, a piece of their multiset union in which every key has the
+// same multiplicity m: the key is then visited once and its softmax weight multiplied by m, which
+// is what visiting it m times adds up to.  log2_mult = log2(m) is added to the scaled score.
+struct KeySeg {
+    int32_t key0, stride, count;
+    float log2_mult;
 };
 struct Tile {
     int32_t h;          // head
@@ -35,6 +43,7 @@ struct HostPlan {
     std::vector<Tile> tiles;
     std::vector<int32_t> rows;
     std::vector<KeySeg> segs;
+    std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs
     std::vector<Item> items;
 };
 

@@ -104,19 +104,35 @@ def test_stage_entry_points_reject_bad_arguments_before_any_gpu_work(B):
     assert merge(N=1 << 22, H=64) == -7                      # one image no longer fits 32-bit counters
 
 
-def _expected_key_sets(N, h, branches, offs):
-    """row -> sorted list of (first key, stride, count), from the definition."""
-    exp = {}
-    for n in range(N):
-        segs = []
-        for x, (w, r) in enumerate(branches):
-            o = (h % r) if offs is None else offs[x][h]
-            first = (n // w) * w + o
-            if n >= first and (n - first) % r == 0:
-                end = min(N, (n // w + 1) * w)
-                segs.append((first, r, len(range(first, end, r))))
-        exp[n] = segs
-    return exp
+def _expected_multiset(N, h, n, branches, offs):
+    """(how often each token is a key of row n, the plain list of (first key, stride, count, 1)), from the
+    definition: one visit per branch that keeps both n and the key in the same part."""
+    counts = np.zeros(N, dtype=np.int32)
+    plain = []
+    for x, (w, r) in enumerate(branches):
+        o = (h % r) if offs is None else offs[x][h]
+        first = (n // w) * w + o
+        if n >= first and (n - first) % r == 0:
+            end = min(N, (n // w + 1) * w)
+            counts[first:end:r] += 1
+            plain.append((first, r, len(range(first, end, r)), 1))
+    return counts, plain
+
+
+def _check_tile_list(N, got, counts, plain):
+    """The tile's progressions add up to the definition's multiset; they are either the plain per-branch list or a
+    coalesced one: disjoint progressions, each of one multiplicity, in fewer 64-key steps than the plain list."""
+    mine = np.zeros(N, dtype=np.int32)
+    visits = np.zeros(N, dtype=np.int32)
+    for (first, stride, count, mult) in got:
+        assert count >= 1 and stride >= 1 and mult >= 1 and 0 <= first and first + stride * (count - 1) < N
+        mine[first:first + stride * count:stride] += mult
+        visits[first:first + stride * count:stride] += 1
+    assert np.array_equal(mine, counts)
+    if sorted(got) != sorted(plain):
+        assert visits.max() == 1
+        steps = lambda lst: sum((c + 63) // 64 for (_, _, c, _) in lst)
+        assert steps(got) < steps(plain) and len(got) <= 32
 
 
 @pytest.mark.parametrize("Bsz,H,N,branches,offs", [
@@ -129,43 +145,48 @@ def _expected_key_sets(N, h, branches, offs):
     # ragged partitions: w does not divide N, w > N, r does not divide w, a last part of one token
     (2, 3, 50, [(16, 3), (7, 2), (64, 5)], None),
     (1, 2, 1025, [(1024, 1), (300, 7)], [[0, 0], [6, 2]]),
+    # the same branch twice: every key counts double
+    (1, 2, 512, [(256, 2), (256, 2), (512, 1)], None),
 ])
 def test_plan_covers_the_definition(B, Bsz, H, N, branches, offs):
     p = B.plan_describe(Bsz, H, N, branches, offs)
     tiles, rows, segs, items = p["tiles"], p["rows"], p["segs"], p["items"]
     seen = np.zeros((H, N), dtype=np.int32)
+    total_pairs = 0
     for (h, rb, nr, sb, ns, _) in tiles:
         assert 1 <= nr <= 256
-        exp = _expected_key_sets(N, h, branches, offs) if N <= 4096 else None
         tile_rows = rows[rb:rb + nr]
         seen[h, tile_rows] += 1
         got = [tuple(int(x) for x in segs[s]) for s in range(sb, sb + ns)]
-        if exp is not None:
-            for n in tile_rows:
-                assert got == exp[int(n)], (h, n)
-        else:
-            for n in tile_rows[[0, -1]]:
-                assert got == _expected_key_sets_row(int(n), h, branches, offs)
+        for n in (tile_rows if N <= 4096 else tile_rows[[0, -1]]):
+            counts, plain = _expected_multiset(N, h, int(n), branches, offs)
+            _check_tile_list(N, got, counts, plain)
+        total_pairs += nr * sum(c * m for (_, _, c, m) in got)
     assert np.all(seen == 1)                                    # every (h, n) in exactly one tile
     assert len(items) % 8 == 0
     real = items[items[:, 0] >= 0]
     pairs = set(map(tuple, real.tolist()))
     assert len(pairs) == len(real) == len(tiles) * Bsz          # every (tile, b) launched once
     assert real[:, 1].min() == 0 and real[:, 1].max() == Bsz - 1
-    total_pairs = 0
-    for (h, rb, nr, sb, ns, _) in tiles:
-        total_pairs += nr * int(segs[sb:sb + ns, 2].sum()) if ns else 0
     if all(N % w == 0 and w % r == 0 for (w, r) in branches):
         assert total_pairs == H * sum(N * w // (r * r) for (w, r) in branches)   # N*w/r^2 pairs per branch
 
 
-def _expected_key_sets_row(n, h, branches, offs):
-    out = []
-    for x, (w, r) in enumerate(branches):
-        o = (h % r) if offs is None else offs[x][h]
-        if n % r == o:
-            out.append(((n // w) * w + o, r, w // r))
-    return out
+def test_plan_visits_a_key_of_several_branches_once(B):
+    """The workload's nested branches (offsets h mod r): a row of all three branches has 3072 (query, key) pairs
+    but only 2048 distinct keys, a row of the first two 2048 and 1536; the plan walks the distinct ones."""
+    N, H, branches = 4096, 12, [(1024, 1), (2048, 2), (4096, 4)]
+    p = B.plan_describe(1, H, N, branches)
+    visited = 0
+    for (h, rb, nr, sb, ns, _) in p["tiles"]:
+        lst = p["segs"][sb:sb + ns]
+        n = int(p["rows"][rb])
+        member = [n % r == h % r for (_, r) in branches]
+        distinct = int(lst[:, 2].sum())
+        assert distinct == {1: 1024, 2: 1536, 3: 2048}[sum(member)]
+        assert int(lst[:, 3].max()) == sum(member)
+        visited += nr * distinct
+    assert visited == H * (2048 * 1024 + 1024 * 1536 + 1024 * 2048)
 
 
 def test_plan_keeps_a_unit_on_one_die_when_there_are_enough_units(B):
@@ -186,7 +207,7 @@ def test_plan_keeps_a_unit_on_one_die_when_there_are_enough_units(B):
 @pytest.mark.parametrize("seed", range(20))
 def test_plan_of_random_problems(B, seed):
     """Random sizes, branch sets (also ragged ones) and offsets: every (h, n) in exactly one tile, and every
-    tile carries exactly the key lists the definition gives its rows."""
+    tile's progressions add up to exactly the multiset of keys the definition gives its rows."""
     rng = np.random.default_rng(50 + seed)
     Bsz, H, N, nb = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(1, 700)), int(rng.integers(1, 9))
     branches, offs = [], []
@@ -199,14 +220,12 @@ def test_plan_of_random_problems(B, seed):
     tiles, rows, segs, items = p["tiles"], p["rows"], p["segs"], p["items"]
     seen = np.zeros((H, N), dtype=np.int32)
     for (h, rb, nr, sb, ns, _) in tiles:
-        assert 1 <= nr <= 256 and ns <= nb
-        exp = _expected_key_sets(N, h, branches, offs)
+        assert 1 <= nr <= 256 and ns <= 32
         got = [tuple(int(x) for x in segs[s]) for s in range(sb, sb + ns)]
         for n in rows[rb:rb + nr]:
             seen[h, n] += 1
-            assert got == exp[int(n)], (h, int(n))
-        for (first, stride, count) in got:
-            assert count >= 1 and 0 <= first and first + stride * (count - 1) < N
+            counts, plain = _expected_multiset(N, h, int(n), branches, offs)
+            _check_tile_list(N, got, counts, plain)
     assert np.all(seen == 1)
     real = items[items[:, 0] >= 0]
     assert len(items) % 8 == 0 and len(set(map(tuple, real.tolist()))) == len(real) == len(tiles) * Bsz
