@@ -357,11 +357,15 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         }
         pf.t = skip;
     }
-    // stage 0 on its way before anything else
+    // the first three stages on their way before anything else
     cursor_load(pf, seg_lds);
     KeyCursor cur = pf;
-    issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr, v_lds_addr);
-    cursor_next(pf, seg_lds, tile.nseg);
+#pragma unroll
+    for (int s = 0; s <= 2; ++s)
+        if (s < n_steps) {
+            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + s * kStageBytes, v_lds_addr + s * kStageBytes);
+            cursor_next(pf, seg_lds, tile.nseg);
+        }
 
     // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
     bf16x8 qf[2][4];
@@ -375,7 +379,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
                 qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
         }
         // pin the fragments here: the compiler then waits for these loads (and, as the counter
-        // is shared, for stage 0) before the main loop and places no vector-memory wait of its
+        // is shared, for the stages issued before them) before the main loop and places no vector-memory wait of its
         // own inside it (it cannot see the copies, and a wait sized for these eight loads would
         // drain the copy pipeline every step)
 #pragma unroll
@@ -383,15 +387,8 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[qb][kk]));
     }
-    wait_vmcnt<0>();
-    // stages 1 and 2 follow; from here on exactly two stages are in flight at every wait
-#pragma unroll
-    for (int s = 1; s <= 2; ++s)
-        if (s < n_steps) {
-            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + s * kStageBytes, v_lds_addr + s * kStageBytes);
-            cursor_next(pf, seg_lds, tile.nseg);
-        }
-    __syncthreads();           // stage 0 complete in LDS
+    wait_vmcnt<0>();           // the Q fragments and, as loads complete in order, all three stages
+    __syncthreads();           // stages 0 to 2 complete in LDS; from the first refill on, two stages are in flight at every wait
 
     // exponent scale, exp(s*x) = exp2(c*x); wave-uniform, so it is kept in a scalar register
     const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale * kLog2e)));
