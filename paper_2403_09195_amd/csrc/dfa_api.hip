@@ -34,6 +34,7 @@ struct DevicePlan {
 
 constexpr int kChipWorkgroupSlots = 512;    // 256 CUs x 2 workgroups of the bf16 forward kernel
 constexpr int kMaxSplit = 4;
+constexpr int kMinShareSteps = 8;           // 64-key steps a workgroup of a split launch should at least walk
 
 std::mutex g_mu;
 std::map<std::vector<int32_t>, DevicePlan> g_plans;
@@ -73,7 +74,15 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     size_t b_split = 0;
     const int64_t rows_total = (int64_t)B * N * H;
     if (hp.items.size() * 2 <= (size_t)kChipWorkgroupSlots) {
-        dp.split = std::min<int>(kMaxSplit, kChipWorkgroupSlots / (int)std::max<size_t>(hp.items.size(), 1));
+        // a share of fewer than kMinShareSteps steps is not worth a partial result and its merge
+        int64_t longest = 0;
+        for (const Tile& t : hp.tiles) {
+            int64_t steps = 0;
+            for (int32_t x = 0; x < t.nseg; ++x) steps += (hp.segs[t.seg_begin + x].count + 63) / 64;
+            longest = std::max(longest, steps);
+        }
+        dp.split = (int32_t)std::min<int64_t>(std::min<int64_t>(kMaxSplit, longest / kMinShareSteps),
+                                              kChipWorkgroupSlots / (int)std::max<size_t>(hp.items.size(), 1));
         if (dp.split >= 2) b_split = align256((size_t)dp.split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float));
         else dp.split = 1;
     }
