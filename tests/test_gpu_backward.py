@@ -37,6 +37,7 @@ CASES = [
     (2, 256, 3, [(64, 2)], None),                                   # uncovered rows
     (1, 512, 4, [(128, 1), (256, 2), (512, 4)], None),              # the workload's branch pattern, scaled down
     (2, 300, 2, [(100, 3), (77, 1), (512, 5)], [[2, 0], [0, 0], [4, 1]]),   # ragged parts, explicit offsets
+    (1, 768, 2, [(192, 2), (384, 3), (768, 1), (768, 1)], None),            # shared keys of multiplicity up to 4
 ]
 
 

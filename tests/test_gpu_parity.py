@@ -196,6 +196,28 @@ def test_ragged_partitions(B, oracle, dtype, N, branches, offs):
     assert np.all(to_f64(out)[dead] == 0.0)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,branches,offs", [
+    (512, [(256, 2), (256, 2), (512, 1)], None),                   # one branch twice: its keys count double
+    (768, [(192, 2), (384, 3), (768, 1)], None),                   # rates 2 and 3: shared keys every 6th row
+    (1024, [(256, 1), (512, 2), (1024, 4), (1024, 8)], None),      # nested rates, multiplicities 1 to 4
+    (640, [(128, 4), (320, 2), (640, 4)], [[1, 1], [1, 1], [1, 3]]),   # explicit offsets: two branches share keys in one head only
+])
+def test_keys_kept_by_several_branches(B, oracle, dtype, N, branches, offs):
+    """Branch sets whose key lists overlap: the launch plan visits a shared key once and weights it by
+    the number of branches that keep it; the oracle visits it once per branch."""
+    H = 2
+    plan = B.plan_describe(2, H, N, branches, offs)
+    assert int(plan["segs"][:, 3].max()) >= 2                      # the case does exercise a multiplicity
+    (q, k, v), ex = make_qkv(340 + N, 2, N, H, 64, dtype)
+    out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
+    if dtype == "bf16":
+        _check_bf16(out, lse, o_ref, l_ref, f"shared keys N={N}")
+    else:
+        _check_f32(out, lse, o_ref, l_ref, f"shared keys N={N}")
+
+
 def test_bf16_reference_exponent_moves_when_logits_keep_growing(B, oracle):
     """Keys ordered so that logits grow along every key list (and jump between lists): the
     reference exponent of the online softmax has to move many times, also late in the walk,
