@@ -181,7 +181,7 @@ int dfa_scatter(const void *og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
  * being a softmax over the multiset union of the branches' keys).
  * Pass NULL arrays to query the sizes only.
  *   n_tiles, n_rows, n_segs, n_items   out, host: entry counts
- *   tiles  host int32 [n_tiles][6] = (h, row_begin, nrows, seg_begin, nseg, unused)
+ *   tiles  host int32 [n_tiles][6] = (h, row_begin, nrows, seg_begin, nseg, 64-key steps of the list)
  *   rows   host int32 [n_rows]     token positions, tile after tile
  *   segs   host int32 [n_segs][4]  = (first key, key stride, key count, multiplicity)
  *   items  host int32 [n_items][2] = (tile or -1 for padding, b) in launch order

@@ -19,7 +19,6 @@ using namespace dfa;
 
 struct DevicePlan {
     void* base = nullptr;
-    const Tile* tiles = nullptr;
     const int32_t* rows = nullptr;
     const KeySeg* segs = nullptr;
     const Item* items = nullptr;
@@ -64,7 +63,6 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     HostPlan hp;
     build_plan(B, H, N, br, nb, offsets, kPlanOrder, &hp);
     if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
-    const size_t b_tiles = align256(hp.tiles.size() * sizeof(Tile));
     const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
     const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
     const size_t b_items = align256(hp.items.size() * sizeof(Item));
@@ -76,38 +74,32 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     if (hp.items.size() * 2 <= (size_t)kChipWorkgroupSlots) {
         // a share of fewer than kMinShareSteps steps is not worth a partial result and its merge
         int64_t longest = 0;
-        for (const Tile& t : hp.tiles) {
-            int64_t steps = 0;
-            for (int32_t x = 0; x < t.nseg; ++x) steps += (hp.segs[t.seg_begin + x].count + 63) / 64;
-            longest = std::max(longest, steps);
-        }
+        for (const Tile& t : hp.tiles) longest = std::max<int64_t>(longest, t.n_steps);
         dp.split = (int32_t)std::min<int64_t>(std::min<int64_t>(kMaxSplit, longest / kMinShareSteps),
                                               kChipWorkgroupSlots / (int)std::max<size_t>(hp.items.size(), 1));
         if (dp.split >= 2) b_split = align256((size_t)dp.split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float));
         else dp.split = 1;
     }
-    if (hipMalloc(&dp.base, b_tiles + b_rows + b_segs + b_items + b_split) != hipSuccess) {
+    if (hipMalloc(&dp.base, b_rows + b_segs + b_items + b_split) != hipSuccess) {
         (void)hipGetLastError();   // reported here; a later launch's check must not see it again
         return DFA_ERR_LAUNCH;
     }
     char* base = static_cast<char*>(dp.base);
     bool ok = true;
-    ok = ok && hipMemcpy(base, hp.tiles.data(), hp.tiles.size() * sizeof(Tile), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(base + b_tiles, hp.rows.data(), hp.rows.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(base, hp.rows.data(), hp.rows.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     if (!hp.segs.empty())
-        ok = ok && hipMemcpy(base + b_tiles + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(base + b_tiles + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(base + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(base + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item), hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) {
         (void)hipFree(dp.base);
         return DFA_ERR_LAUNCH;
     }
-    dp.tiles = reinterpret_cast<const Tile*>(base);
-    dp.rows = reinterpret_cast<const int32_t*>(base + b_tiles);
-    dp.segs = reinterpret_cast<const KeySeg*>(base + b_tiles + b_rows);
-    dp.items = reinterpret_cast<const Item*>(base + b_tiles + b_rows + b_segs);
+    dp.rows = reinterpret_cast<const int32_t*>(base);
+    dp.segs = reinterpret_cast<const KeySeg*>(base + b_rows);
+    dp.items = reinterpret_cast<const Item*>(base + b_rows + b_segs);
     dp.n_items = (int32_t)hp.items.size();
     if (dp.split >= 2) {
-        dp.split_out = reinterpret_cast<float*>(base + b_tiles + b_rows + b_segs + b_items);
+        dp.split_out = reinterpret_cast<float*>(base + b_rows + b_segs + b_items);
         dp.split_lse = dp.split_out + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
     }
     try {
@@ -188,7 +180,7 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
     p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
     p.out = out; p.lse = lse;
-    p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
+    p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
     p.H = H; p.N = N; p.scale = scale;
     p.split = 1; p.part_rows = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -356,7 +348,7 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
         p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
         p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
         p.lse = lse; p.delta = delta_ws; p.lse2 = delta_ws + (int64_t)B * H * N; p.dq = dq; p.dk = dk; p.dv = dv;
-        p.tiles = dp.tiles; p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
+        p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
         p.H = H; p.N = N; p.scale = scale;
         return launch_bwd(p, dp.n_items, B, dt == DFA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess
                    ? DFA_OK : DFA_ERR_LAUNCH;
@@ -428,7 +420,7 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
         if (tiles)
             for (size_t t = 0; t < hp.tiles.size(); ++t) {
                 const Tile& x = hp.tiles[t];
-                const int32_t rec[6] = {x.h, x.row_begin, x.nrows, x.seg_begin, x.nseg, 0};
+                const int32_t rec[6] = {x.h, x.row_begin, x.nrows, x.seg_begin, x.nseg, x.n_steps};
                 std::memcpy(tiles + 6 * t, rec, sizeof(rec));
             }
         if (rows) std::memcpy(rows, hp.rows.data(), hp.rows.size() * sizeof(int32_t));

@@ -132,7 +132,7 @@ void bwd_kernel(const BwdParams p) {
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const Tile tile = p.tiles[item.tile];
+    const Tile tile = item.t;
     const int tid = threadIdx.x;
     const int h = tile.h, b = item.b;
     const bool live = tid < tile.nrows;

@@ -132,7 +132,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const Tile tile = p.tiles[item.tile];
+    const Tile tile = item.t;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int h = tile.h, b = item.b;
@@ -176,9 +176,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
     const int frag_a = j * kRowElems + 8 * (g ^ k_swizzle(j));
     const int frag_t = (((lane & 15) >> 2) + 8 * g) * kRowElems + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    int n_steps = 0;
-    for (int s = 0; s < tile.nseg; ++s)
-        n_steps += (__builtin_amdgcn_readfirstlane(seg_lds[s].count) + kKeyTile - 1) / kKeyTile;
+    int n_steps = tile.n_steps;
 
     const uint32_t t_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &t_lds[0][0][0]);
     constexpr uint32_t kStageBytes = kStageElems * 2, kTensorBytes = kBwdStages * kStageBytes;
@@ -349,7 +347,7 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
-    const Tile tile = p.tiles[item.tile];
+    const Tile tile = item.t;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int h = tile.h, b = item.b;
@@ -390,9 +388,7 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
     const int frag_a = j * kRowElems + 8 * (g ^ k_swizzle(j));
     const int frag_t = (((lane & 15) >> 2) + 8 * g) * kRowElems + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    int n_steps = 0;
-    for (int s = 0; s < tile.nseg; ++s)
-        n_steps += (__builtin_amdgcn_readfirstlane(seg_lds[s].count) + kKeyTile - 1) / kKeyTile;
+    int n_steps = tile.n_steps;
 
     const uint32_t t_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &t_lds[0][0][0]);
     const uint32_t sc_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &sc_lds[0][0][0]);

@@ -25,7 +25,6 @@ struct FwdParams {
     int64_t svb, svn, svh;
     void* out;          // [B, N, H, D] contiguous
     float* lse;         // [B, H, N] or nullptr
-    const Tile* tiles;
     const int32_t* rows;
     const KeySeg* segs;
     const Item* items;
@@ -54,7 +53,6 @@ struct BwdParams {
     void* dq;
     void* dk;
     void* dv;
-    const Tile* tiles;
     const int32_t* rows;
     const KeySeg* segs;
     const Item* items;

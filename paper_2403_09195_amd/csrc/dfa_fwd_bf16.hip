@@ -278,13 +278,35 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     const int part = kSplit ? (int)(blockIdx.x % (unsigned)p.split) : 0;
     const Item item = p.items[kSplit ? blockIdx.x / (unsigned)p.split : blockIdx.x];
     if (item.tile < 0) return;
-    const Tile tile = p.tiles[item.tile];
+    const Tile tile = item.t;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int h = tile.h, b = item.b;
 
-    row_idx[tid] = p.rows[tile.row_begin + min(tid, tile.nrows - 1)];
-    if (tid < tile.nseg) seg_lds[tid] = p.segs[tile.seg_begin + tid];
+    // What the tile's start waits for, in as few round trips as the data allows: the row numbers (this
+    // thread's entry of the tile's list and the two rows whose Q fragments this lane holds) and the key
+    // progressions in one go, then the Q fragments, which go out before anything else: theirs is the
+    // longest wait, and the set-up of the K/V stages below runs under it.  (The plan's progression
+    // array ends with one spare entry, so a tile without progressions still reads inside it.)
+    const int32_t my_row = p.rows[tile.row_begin + min(tid, tile.nrows - 1)];
+    const int32_t q_row[2] = {p.rows[tile.row_begin + min(wave * 64 + j, tile.nrows - 1)],
+                              p.rows[tile.row_begin + min(wave * 64 + 32 + j, tile.nrows - 1)]};
+    KeySeg my_seg = p.segs[tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)];
+    // held here so that the compiler does not move this load behind the Q loads (whose wait would then
+    // sit in front of the barrier)
+    asm volatile("" : "+v"(my_seg.key0), "+v"(my_seg.stride), "+v"(my_seg.count), "+v"(my_seg.log2_mult));
+    // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
+    bf16x8 qf[2][4];
+    {
+        const uint16_t* qp = static_cast<const uint16_t*>(p.q) + (int64_t)item.b * p.sqb + (int64_t)tile.h * p.sqh;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + (int64_t)q_row[qb] * p.sqn + 16 * kk + 8 * g);
+    }
+    row_idx[tid] = my_row;
+    if (tid < tile.nseg) seg_lds[tid] = my_seg;
     __syncthreads();
 
     OutT* const out = static_cast<OutT*>(p.out) + (kSplit ? part * p.part_rows * kD : 0);
@@ -329,9 +351,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     };
     const FragLane fl = frag_lane(lane);
 
-    int n_steps = 0;
-    for (int s = 0; s < tile.nseg; ++s)
-        n_steps += (__builtin_amdgcn_readfirstlane(seg_lds[s].count) + kKeyTile - 1) / kKeyTile;
+    int n_steps = tile.n_steps;
 
     const uint32_t k_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &k_lds[0][0]);
     const uint32_t v_lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &v_lds[0][0]);
@@ -367,27 +387,15 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             cursor_next(pf, seg_lds, tile.nseg);
         }
 
-    // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
-    bf16x8 qf[2][4];
-    {
-        const uint16_t* qp = static_cast<const uint16_t*>(p.q) + (int64_t)b * p.sqb + (int64_t)h * p.sqh;
+    // pin the Q fragments here: the compiler then waits for their loads (and, as the counter is
+    // shared and loads complete in order, for the stages issued after them) before the main loop and
+    // places no vector-memory wait of its own inside it (it cannot see the copies, and a wait sized
+    // for these eight loads would drain the copy pipeline every step)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int64_t row = row_idx[wave * 64 + qb * 32 + j];
+    for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
-        }
-        // pin the fragments here: the compiler then waits for these loads (and, as the counter
-        // is shared, for the stages issued before them) before the main loop and places no vector-memory wait of its
-        // own inside it (it cannot see the copies, and a wait sized for these eight loads would
-        // drain the copy pipeline every step)
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[qb][kk]));
-    }
-    wait_vmcnt<0>();           // the Q fragments and, as loads complete in order, all three stages
+        for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[qb][kk]));
+    wait_vmcnt<0>();           // all three stages
     __syncthreads();           // stages 0 to 2 complete in LDS; from the first refill on, two stages are in flight at every wait
 
     // exponent scale, exp(s*x) = exp2(c*x); wave-uniform, so it is kept in a scalar register

@@ -168,7 +168,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             plan->seg_mult.insert(plan->seg_mult.end(), list_mult.begin(), list_mult.end());
             for (size_t lo = 0; lo < rows.size(); lo += kTileRows) {
                 const int32_t cnt = (int32_t)std::min<size_t>(kTileRows, rows.size() - lo);
-                Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, 0};
+                Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, (int32_t)steps_of(list)};
                 plan->rows.insert(plan->rows.end(), rows.begin() + lo, rows.begin() + lo + cnt);
                 plan->tiles.push_back(t);
                 tile_cost.push_back(keys * cnt);
@@ -197,7 +197,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
         for (int32_t b = 0; b < B; ++b)
             for (int32_t h = 0; h < H; ++h) {
                 const int d = lightest();
-                for (int32_t t : tiles_of_head[h]) per_die[d].push_back(Item{t, b});
+                for (int32_t t : tiles_of_head[h]) per_die[d].push_back(Item{t, b, plan->tiles[t]});
                 die_cost[d] += head_cost[h];
             }
     } else {
@@ -208,7 +208,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
         for (int32_t t : order)
             for (int32_t b = 0; b < B; ++b) {
                 const int d = lightest();
-                per_die[d].push_back(Item{t, b});
+                per_die[d].push_back(Item{t, b, plan->tiles[t]});
                 die_cost[d] += std::max<int64_t>(tile_cost[t], 1);
             }
     }
@@ -244,7 +244,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
     plan->items.reserve(longest * kNumXcd);
     for (size_t p = 0; p < longest; ++p)
         for (int d = 0; d < kNumXcd; ++d)
-            plan->items.push_back(p < per_die[d].size() ? per_die[d][p] : Item{-1, 0});
+            plan->items.push_back(p < per_die[d].size() ? per_die[d][p] : Item{-1, 0, Tile{0, 0, 0, 0, 0, 0}});
 }
 
 }  // namespace dfa

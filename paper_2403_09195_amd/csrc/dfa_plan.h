@@ -32,11 +32,12 @@ struct Tile {
     int32_t nrows;      // 1 .. kTileRows
     int32_t seg_begin;  // first entry in the key-segment list
     int32_t nseg;       // 0 = rows kept by no branch (output 0, lse -inf)
-    int32_t pad;
+    int32_t n_steps;    // 64-key steps of the whole list: sum of ceil(count / 64)
 };
 struct Item {        // one workgroup of the launch
     int32_t tile;    // -1 = padding, nothing to do
     int32_t b;       // batch index
+    Tile t;          // copy of tiles[tile]: a workgroup reads what it needs to start in one load
 };
 
 struct HostPlan {
