@@ -114,6 +114,32 @@ def sweep_report(binding, synth, torch, np, steps, warmup):
                                     "computes N^2 pairs per head, the three branches 7*N^2/16"}
 
 
+def tile_cost_report(binding, synth, torch, np):
+    """What a 64-key step and what a tile cost: single-branch launches (w, 1) on the throughput shape give
+    16 * B * H tiles of w / 64 steps each; with 512 workgroup slots on the chip a launch then takes about
+    c + (tiles / 512) * (per_tile + steps * per_step).  Least squares over two batch sizes and five w."""
+    H, N, D, scale = 12, 4096, 64, 0.125
+    rows, A, y = [], [], []
+    for Bsz in (16, 32):
+        st, _ = synth.qkv(synth.BASE_SEED + 40 + Bsz, Bsz, N, H, D, "bf16")
+        q, k, v = (torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda() for a in st)
+        out = torch.empty_like(q)
+        lse = torch.empty((Bsz, H, N), dtype=torch.float32, device="cuda")
+        for w in (256, 512, 1024, 2048, 4096):
+            br = [(w, 1)]
+            for _ in range(3):
+                binding.forward(q, k, v, br, scale, out=out, lse=lse)
+            us = 1e3 * min(binding.forward_timed(q, k, v, br, scale, 30, out=out, lse=lse) for _ in range(3))
+            per_slot = Bsz * H * (N // 256) / 512.0
+            rows.append({"B": Bsz, "w": w, "steps_per_tile": w // 64, "tiles_per_slot": per_slot, "launch_us": us})
+            A.append([1.0, per_slot, per_slot * (w // 64)])
+            y.append(us)
+        del q, k, v, out, lse
+    coef, *_ = np.linalg.lstsq(np.array(A), np.array(y), rcond=None)
+    return {"tile_cost": rows, "fit_us": {"per_launch": coef[0], "per_tile_and_slot": coef[1], "per_step_and_slot": coef[2]},
+            "note": "two workgroup slots share a CU; launch_us is the best HIP-event mean of three runs of 30 launches"}
+
+
 def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=12, H=12):
     """The encoder attention stack: 12 layers, embed 768 = 12 heads x 64, B = 8 images of 4096 tokens, bf16;
     per layer QKV projection (768 -> 2304), dilated attention, output projection (768 -> 768); weights
@@ -214,6 +240,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="input-size sweep of the paper's ablation (256^2, 512^2, 1024^2 images; 6 and 12 heads): "
                          "dilated attention against dense attention in the same kernel (w = N, r = 1)")
+    ap.add_argument("--tile-cost", action="store_true",
+                    help="single-branch launches of growing segment length on the throughput shape: cost per 64-key "
+                         "step and per tile of the forward kernel")
     ap.add_argument("--backward", action="store_true",
                     help="time dfa_backward (dq, dk, dv) on --workload")
     ap.add_argument("--zero-inputs", action="store_true",
@@ -256,6 +285,9 @@ def main():
         return
     if args.sweep:
         print(json.dumps(sweep_report(binding, synth, torch, np, args.steps, args.warmup)))
+        return
+    if args.tile_cost:
+        print(json.dumps(tile_cost_report(binding, synth, torch, np)))
         return
 
     cfg = synth.CONFIGS[args.workload]
