@@ -51,3 +51,37 @@ def multiset_attention(q, k, v, scale, branches, head_offsets=None):
 
 def randn(rng, *shape):
     return rng.standard_normal(shape)
+
+
+def multiset_attention_backward(q, k, v, dout, scale, branches, head_offsets=None):
+    """Chain rule on the multiset softmax, written with dense matrices per (b, h):
+      P = mult * exp(scale q k^T - lse),  out = P v,  delta = rowsum(dout * out),  dP = dout v^T,
+      dS = P * (dP - delta),  dq = scale dS k,  dk = scale dS^T q,  dv = P^T dout.
+    Returns (dq, dk, dv, dq_abs, dk_abs, dv_abs), all [B, N, H, D] fp64.  The *_abs arrays are the same sums
+    over absolute values of their terms, with |dP - delta| bounded by |dP| + rowsum(|dout * out|): what a
+    rounding error of relative size eps in every term can at most add up to is eps times them."""
+    B, N, H, D = q.shape
+    res = [np.zeros((B, N, H, D)) for _ in range(6)]
+    for h in range(H):
+        mult = multiplicity_matrix(N, h, branches, head_offsets).astype(np.float64)
+        has = mult.sum(axis=1) > 0
+        for b in range(B):
+            qh, kh, vh, gh = q[b, :, h], k[b, :, h], v[b, :, h], dout[b, :, h]
+            s = scale * (qh @ kh.T)
+            m = np.where(has, np.where(mult > 0, s, -np.inf).max(axis=1, initial=-np.inf), 0.0)
+            e = mult * np.exp(np.minimum(s - m[:, None], 700.0) * (mult > 0))
+            l = e.sum(axis=1)
+            P = e / np.where(has, l, 1.0)[:, None]
+            out = P @ vh
+            delta = (gh * out).sum(axis=1)
+            delta_abs = np.abs(gh * out).sum(axis=1)
+            dP = gh @ vh.T
+            dS = P * (dP - delta[:, None])
+            W = P * (np.abs(dP) + delta_abs[:, None])
+            res[0][b, :, h] = scale * (dS @ kh)
+            res[1][b, :, h] = scale * (dS.T @ qh)
+            res[2][b, :, h] = P.T @ gh
+            res[3][b, :, h] = scale * (W @ np.abs(kh))
+            res[4][b, :, h] = scale * (W.T @ np.abs(qh))
+            res[5][b, :, h] = P.T @ np.abs(gh)
+    return tuple(res)

@@ -3,6 +3,7 @@ forward and backward entry points against the oracle: shapes nobody picked by ha
 import numpy as np
 import pytest
 
+import helpers
 from gpu_util import check_lse, error_stats, make_qkv, to_device, to_f64
 
 pytestmark = pytest.mark.gpu
@@ -31,7 +32,7 @@ def _problem(seed):
     return Bsz, N, H, branches, (offs if seed % 2 else None)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_problem_forward_and_backward(B, oracle, seed):
     from paper_2403_09195_amd import synth
     Bsz, N, H, branches, offs = _problem(seed)
@@ -53,17 +54,22 @@ def test_random_problem_forward_and_backward(B, oracle, seed):
         g = to_device(st)
         dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125, head_offsets=offs)
         refs = oracle.backward(*ex, ge, branches, 0.125, head_offsets=offs)
-        for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        # size of the terms each gradient element is a sum of (dense numpy, independent of oracle and kernels)
+        bounds = helpers.multiset_attention_backward(*ex, ge, 0.125, branches, offs)[3:]
+        for name, got, ref, absum in zip(("dq", "dk", "dv"), (dq, dk, dv), refs, bounds):
             d = np.abs(to_f64(got) - ref)
             if dtype == "f32":
                 assert d.max() <= 2e-5 * max(1.0, np.abs(ref).max()), name
             else:
-                # Rows differ widely here (a row with a short list has a sharp softmax and large gradients, one
-                # with long lists small ones), so each row is held to its own size: per element
-                # |err| <= 2^-8 |g| + 3e-2 rms(row), and the mean error of a row <= 2^-7 rms(row) + 1e-5: a row with a
-                # dozen keys averages nothing, so the bf16 roundings of P, dS, the forward's out (through delta) and
-                # the result, 2^-9 each, add up (measured worst 0.0044 rms(row), on 13-key rows).
-                row_rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
-                assert np.all(d <= 2.0 ** -8 * np.abs(ref) + 3e-2 * row_rms + 1e-5), name
-                assert np.all(d.mean(axis=-1, keepdims=True) <= 2.0 ** -7 * row_rms + 1e-5), name
+                # A gradient element is a sum of terms that each carry bf16 roundings of relative size eps = 2^-9:
+                # P or dS rounded for the second product, delta taken from the rounded forward output, and the
+                # result's own rounding.  Rows differ widely in size (short lists: sharp softmax, large terms) and
+                # sums cancel, so the bar is the forward bound eps * sum|terms| of each element, not a fraction
+                # of the result: |err| <= 2^-8 |g| + 4 eps sum|terms| per element (worst seen over 132 seeds: 1.5 eps),
+                # 4 eps on a row's mean (worst 1.7), and eps on the mean over the tensor, where the roundings
+                # average out (worst 0.42).  Elements with no term at all must come out as zero.
+                eps = 2.0 ** -9
+                assert np.all(d <= 2.0 ** -8 * np.abs(ref) + 4 * eps * absum + 1e-6), name
+                assert np.all(d.mean(axis=-1) <= 4 * eps * absum.mean(axis=-1) + 1e-6), name
+                assert d.mean() <= eps * absum.mean() + 1e-7, name
             assert np.all(to_f64(got)[dead] == 0.0)

@@ -7,6 +7,7 @@ import os
 import numpy as np
 import pytest
 
+import helpers
 from helpers import dense_softmax_attention, multiset_attention, multiplicity_matrix
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -433,6 +434,24 @@ def test_backward_matches_central_differences_of_the_forward(oracle, N, branches
             x[idx] = old
             num[idx] = (lp - lm) / (2 * eps)
         assert np.abs(num - g).max() < 1e-7, (name, float(np.abs(num - g).max()))
+
+
+@pytest.mark.parametrize("Bsz,N,H,branches,offs", [
+    (2, 96, 3, [(32, 2), (48, 3), (96, 1)], None),
+    (1, 150, 2, [(144, 3), (69, 3)], [[1, 2], [0, 2]]),              # ragged parts, explicit offsets
+    (2, 64, 2, [(16, 1), (16, 1), (64, 4)], None),                   # a branch twice
+    (1, 70, 1, [(35, 7)], None),                                     # rows that nothing keeps
+])
+def test_backward_equals_the_dense_chain_rule(oracle, Bsz, N, H, branches, offs):
+    """The oracle's pair loops against the same chain rule written with dense N x N matrices in numpy
+    (multiplicity matrix from the definition, P = mult * exp(s - lse), dS = P (dP - delta))."""
+    rng = np.random.default_rng(77 + N)
+    q, k, v, g = (helpers.randn(rng, Bsz, N, H, 64) for _ in range(4))
+    ref = helpers.multiset_attention_backward(q, k, v, g, 0.125, branches, offs)
+    got = oracle.backward(q, k, v, g, branches, 0.125, head_offsets=offs)
+    for a, b, bound in zip(got, ref[:3], ref[3:]):
+        assert np.abs(a - b).max() <= 1e-12
+        assert np.all(np.abs(b) <= bound + 1e-12)                    # the absolute-term sums do bound the sums
 
 
 def test_backward_special_cases(oracle):
