@@ -73,3 +73,39 @@ def test_random_problem_forward_and_backward(B, oracle, seed):
                 assert np.all(d.mean(axis=-1) <= 4 * eps * absum.mean(axis=-1) + 1e-6), name
                 assert d.mean() <= eps * absum.mean() + 1e-7, name
             assert np.all(to_f64(got)[dead] == 0.0)
+
+
+def _many_branch_problem(seed):
+    """Up to eight branches on a few thousand tokens; every third problem with nested power-of-two rates and
+    segment lengths (the workloads' pattern: many shared keys), the others with arbitrary ones."""
+    rng = np.random.default_rng(7000 + seed)
+    H = int(rng.integers(1, 4))
+    N = int(rng.integers(300, 5000))
+    nb = int(rng.integers(2, 9))
+    nested = seed % 3 == 0
+    branches, offs = [], []
+    for _ in range(nb):
+        r = int(rng.choice([1, 2, 4, 8, 16])) if nested else int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16]))
+        w = int(rng.choice([64, 128, 256, 512, 1024, 2048, 4096])) if nested else int(rng.integers(max(r, 16), 2 * N))
+        branches.append((w, r))
+        offs.append([int(rng.integers(0, r)) for _ in range(H)])
+    return N, H, branches, (None if nested or seed % 2 == 0 else offs)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_problem_with_many_branches_forward(B, oracle, seed):
+    """Keys kept by up to eight branches at once: the plans of these problems carry multiplicities up to 8."""
+    N, H, branches, offs = _many_branch_problem(seed)
+    print(f"[many branches {seed}] N={N} H={H} branches={branches} offsets={offs}", flush=True)
+    for dtype in ("bf16", "f32"):
+        (q, k, v), ex = make_qkv(3000 + seed, 1, N, H, 64, dtype)
+        out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
+        o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
+        mx, mean = error_stats(to_f64(out), o_ref)
+        if dtype == "bf16":
+            check_lse(to_f64(lse), l_ref, atol=2e-3)
+            assert mx <= 2e-2 and mean <= 2e-3
+        else:
+            check_lse(to_f64(lse), l_ref, atol=1e-5, rtol=1e-5)
+            assert mx <= 1e-5
+        assert np.all(to_f64(out)[np.isneginf(l_ref).transpose(0, 2, 1)] == 0.0)
