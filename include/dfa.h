@@ -35,7 +35,8 @@
  *   - dfa_forward / dfa_forward_branch keep a small per-process cache of launch plans
  *     (tile lists in device memory, a few hundred KB each), keyed by device and problem
  *     shape.  The first call with a new shape allocates and uploads its plan
- *     (synchronously); later calls with that shape allocate nothing.
+ *     (synchronously); later calls with that shape allocate nothing and only enqueue
+ *     kernels, so they can be recorded into a HIP graph (call once before capturing).
  *     dfa_release_plans() frees them.  A bf16 dfa_forward whose plan has fewer workgroups than the
  *     chip has compute units (a single image, say) walks every tile with several workgroups and
  *     merges their fp32 partial results; those live in the plan too (up to 4 x B*N*H*65 floats),

@@ -274,6 +274,39 @@ def test_bf16_side_stream_and_plan_release(B, oracle):
     assert bool((out4 == out0).all())
 
 
+@pytest.mark.parametrize("Bsz,N,H", [(4, 1024, 6), (1, 2048, 3)])
+def test_forward_and_backward_replay_from_a_captured_graph(B, Bsz, N, H):
+    """Once a shape's plan exists the calls only enqueue kernels, so they can be captured in a HIP graph: the
+    graph is replayed on fresh inputs, with eager work and synchronisations in between, and every replay must
+    equal the eager call on the same inputs bit for bit (the second shape takes the split launch and its merge)."""
+    import torch
+    from paper_2403_09195_amd import synth
+    branches = [(N // 4, 1), (N // 2, 2), (N, 4)]
+    mk = lambda seed: make_qkv(seed, Bsz, N, H, 64, "bf16")[0]
+    q, k, v = mk(900)
+    g = to_device(synth.tensor(900, 7, (Bsz, N, H, 64), "bf16")[0])
+    out, lse = B.forward(q, k, v, branches, 0.125)                     # builds the plan
+    dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.forward(q, k, v, branches, 0.125, out=out, lse=lse)
+        grads = B.backward(q, k, v, out, lse, g, branches, 0.125)
+    for rep in range(3):
+        nq, nk, nv = mk(901 + rep)
+        q.copy_(nq); k.copy_(nk); v.copy_(nv)
+        out.zero_(); lse.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        e_out, e_lse = B.forward(nq, nk, nv, branches, 0.125)
+        e_grads = B.backward(nq, nk, nv, e_out, e_lse, g, branches, 0.125)
+        torch.cuda.synchronize()
+        assert bool((out == e_out).all()) and bool((lse == e_lse).all()), rep
+        for a, b in zip(grads, e_grads):
+            assert bool((a == b).all()), rep
+
+
 def test_bf16_reads_packed_qkv_through_strides(B, oracle):
     import torch
     from paper_2403_09195_amd import synth
