@@ -38,7 +38,7 @@ constexpr int kMinShareSteps = 8;           // 64-key steps a workgroup of a spl
 std::mutex g_mu;
 std::map<std::vector<int32_t>, DevicePlan> g_plans;
 
-constexpr int kPlanOrder = 2;   // launch order of build_plan (see dfa_plan.cpp)
+constexpr int kPlanOrder = 3;   // launch order of build_plan (see dfa_plan.cpp)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 

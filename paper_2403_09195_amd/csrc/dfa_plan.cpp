@@ -212,12 +212,17 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 die_cost[d] += std::max<int64_t>(tile_cost[t], 1);
             }
     }
-    // Order inside a die.  Mode 2 (default): the multi-branch tiles of one (b, h) stay together,
-    // heaviest first, so that the workgroups running at the same time read the same K/V rows
-    // from the die's L2; the cheap single-branch tiles of all units follow as filler for the
-    // end of the launch.  Mode 1: strictly unit after unit.  Mode 0: heaviest first overall.
+    // Order inside a die.  Mode 3 (default): unit after unit, each unit's tiles heaviest first, so
+    // that the workgroups running at the same time read the same K/V rows from the die's L2 and
+    // every row comes from HBM about once; only the last kTailItemsPerDie items of the die are
+    // ordered heaviest first as one group, so that the launch ends on short tiles (long lists only).  Mode 2: the
+    // multi-progression tiles of one unit together, the single-progression tiles of all units
+    // last as filler.  Mode 1: strictly unit after unit.  Mode 0: heaviest first overall.
     size_t longest = 0;
     for (auto& v : per_die) {
+        // a die with fewer than four items per workgroup slot is too short a list for mode 3's
+        // unit-after-unit body to balance: it gets mode 2
+        if (order_mode == 3 && v.size() < 4 * (size_t)kSlotsPerDie) order_mode = 2;
         if (order_mode == 0 || !by_unit) {
             std::stable_sort(v.begin(), v.end(), [&](const Item& a, const Item& c) {
                 return tile_cost[a.tile] > tile_cost[c.tile];
@@ -238,6 +243,12 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             if (order_mode == 2)
                 std::stable_partition(v.begin(), v.end(),
                                       [&](const Item& a) { return plan->tiles[a.tile].nseg > 1; });
+            if (order_mode == 3) {
+                const size_t tail = std::min<size_t>(v.size(), kTailItemsPerDie);
+                std::stable_sort(v.end() - tail, v.end(), [&](const Item& a, const Item& c) {
+                    return tile_cost[a.tile] > tile_cost[c.tile];
+                });
+            }
         }
         longest = std::max(longest, v.size());
     }

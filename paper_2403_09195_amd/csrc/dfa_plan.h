@@ -14,6 +14,8 @@ namespace dfa {
 
 constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
 constexpr int kNumXcd = 8;       // MI355X: 8 accelerator dies, workgroups dealt round-robin
+constexpr int kSlotsPerDie = 64;         // workgroups of the forward kernel that run at once on one die (32 CUs x 2)
+constexpr int kTailItemsPerDie = 96;     // launch order: items at the end of a die's list that go heaviest first
 constexpr int kMaxTileSegs = 32; // key progressions per tile (the kernels hold a tile's list in LDS)
 constexpr int kMaxCoalesceLcm = 64;   // largest common period of a tile's dilation rates that is coalesced
 
@@ -57,7 +59,7 @@ inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t
 }
 
 // Builds tiles, row lists, key segments and the launch order for B images.
-// order_mode: 2 = default (see dfa_plan.cpp), 0 and 1 are alternatives kept for measurement.
+// order_mode: 3 = default (see dfa_plan.cpp), 0 to 2 are alternatives kept for measurement.
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
                 const int32_t* offsets, int order_mode, HostPlan* plan);
 
