@@ -204,6 +204,24 @@ def test_plan_keeps_a_unit_on_one_die_when_there_are_enough_units(B):
     assert per_die.min() == per_die.max() == 24
 
 
+def test_plan_runs_the_tiles_of_a_unit_together_on_long_lists(B):
+    """Throughput workload: 384 items per die.  Outside the last 96 items of a die's list (which go heaviest
+    first) the 16 tiles of a (b, h) unit follow one another, heaviest first."""
+    p = B.plan_describe(16, 12, 4096, [(1024, 1), (2048, 2), (4096, 4)])
+    items, tiles = p["items"], p["tiles"]
+    for die in range(8):
+        lst = [(int(t), int(b)) for (t, b) in items[die::8] if t >= 0]
+        assert len(lst) == 384
+        body, tail = lst[:-96], lst[-96:]
+        units = [(b, int(tiles[t][0])) for (t, b) in body]
+        for lo in range(0, len(body), 16):
+            assert len(set(units[lo:lo + 16])) == 1                       # one unit per run of 16
+            steps = [int(tiles[t][5]) for (t, _) in body[lo:lo + 16]]
+            assert steps == sorted(steps, reverse=True)
+        steps = [int(tiles[t][5]) * int(tiles[t][2]) for (t, _) in tail]
+        assert steps == sorted(steps, reverse=True)
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_plan_of_random_problems(B, seed):
     """Random sizes, branch sets (also ragged ones) and offsets: every (h, n) in exactly one tile, and every
