@@ -124,7 +124,7 @@ int dfa_forward(const void *q, const void *k, const void *v,
  *   q, k, v, strides, shapes, dt, scale, branches, head_offsets   exactly as passed to dfa_forward
  *   out, lse       device, what dfa_forward returned (out dtype dt [B, N, H, D], lse fp32 [B, H, N])
  *   dout           device, dtype dt, contiguous [B, N, H, D]
- *   delta_ws       device, fp32 [2][B, H, N] workspace (receives dout . out and lse * log2(e) per row)
+ *   delta_ws       device, fp32 [2][B, H, N] workspace (receives -(dout . out) and lse * log2(e) per row)
  *   dq, dk, dv     device, dtype dt, contiguous [B, N, H, D]; rows kept by no branch get 0
  * dt = DFA_BF16: bf16 operands on the matrix cores, fp32 accumulation, P and dS rounded to bf16
  * before their second products, gradients rounded to bf16.  dt = DFA_F32: fp32 vector arithmetic

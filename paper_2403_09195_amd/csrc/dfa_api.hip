@@ -347,7 +347,7 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
         p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
         p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
         p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
-        p.lse = lse; p.delta = delta_ws; p.lse2 = delta_ws + (int64_t)B * H * N; p.dq = dq; p.dk = dk; p.dv = dv;
+        p.lse = lse; p.ndelta = delta_ws; p.lse2 = delta_ws + (int64_t)B * H * N; p.dq = dq; p.dk = dk; p.dv = dv;
         p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
         p.H = H; p.N = N; p.scale = scale;
         return launch_bwd(p, dp.n_items, B, dt == DFA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess

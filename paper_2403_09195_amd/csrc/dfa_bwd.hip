@@ -80,11 +80,11 @@ __device__ __forceinline__ void axpy_row(float s, const float* b, float (&acc)[k
     }
 }
 
-// delta[b][h][n] = dout[b][n][h][:] . out[b][n][h][:] and lse2 = lse * log2(e); 16 lanes per row, 4 d each.
+// ndelta[b][h][n] = -(dout[b][n][h][:] . out[b][n][h][:]) and lse2 = lse * log2(e); 16 lanes per row, 4 d each.
 // grid = (16 * rows of one image / 256, B): one image is indexed with 32-bit arithmetic.
 template <typename T>
 __global__ __launch_bounds__(256)
-void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* delta, float* lse2, int32_t H, int32_t N) {
+void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* ndelta, float* lse2, int32_t H, int32_t N) {
     const uint32_t x = blockIdx.x * 256u + threadIdx.x;
     const uint32_t t = x >> 4;                                       // n * H + h
     const int part = (int)(x & 15u);
@@ -101,7 +101,7 @@ void bwd_delta_kernel(const T* out, const T* dout, const float* lse, float* delt
     if (in && part == 0) {
         const uint32_t n = t / (uint32_t)H, h = t - n * (uint32_t)H;
         const int64_t at = (b * H + h) * N + n;
-        delta[at] = s;
+        ndelta[at] = -s;
         lse2[at] = lse[at] * kLog2e;
     }
 }
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256)
 void bwd_kernel(const BwdParams p) {
     __shared__ __attribute__((aligned(16))) float a_lds[kKeyTile * kD];   // k rows (mode 0) or q rows (modes 1, 2)
     __shared__ __attribute__((aligned(16))) float b_lds[kKeyTile * kD];   // v rows (mode 0) or dout rows
-    __shared__ float l_lds[kKeyTile], d_lds[kKeyTile];                     // lse and delta of the staged queries
+    __shared__ float l_lds[kKeyTile], d_lds[kKeyTile];                     // lse and -delta of the staged queries
 
     const Item item = p.items[blockIdx.x];
     if (item.tile < 0) return;
@@ -153,7 +153,7 @@ void bwd_kernel(const BwdParams p) {
     const T* const vb = static_cast<const T*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
     const T* const gb = static_cast<const T*>(p.dout) + ((int64_t)b * p.N * p.H + h) * kD;   // row n at n * H * D
     const float* const lse_bh = p.lse + ((int64_t)b * p.H + h) * p.N;
-    const float* const delta_bh = p.delta + ((int64_t)b * p.H + h) * p.N;
+    const float* const ndelta_bh = p.ndelta + ((int64_t)b * p.H + h) * p.N;
 
     float x0[kD], x1[kD];                    // mode 0: q, dout of this row; mode 1: k; mode 2: k, v
     float my_l = 0.f, my_d = 0.f;
@@ -161,7 +161,7 @@ void bwd_kernel(const BwdParams p) {
         load_row<T>(qb + n * p.sqn, x0);
         load_row<T>(gb + n * p.H * kD, x1);
         my_l = lse_bh[n] * kLog2e;
-        my_d = delta_bh[n];
+        my_d = ndelta_bh[n];
     } else {
         load_row<T>(kb + n * p.skn, x0);
         if (kMode == 2) load_row<T>(vb + n * p.svn, x1);
@@ -180,7 +180,7 @@ void bwd_kernel(const BwdParams p) {
                 if (tid < kKeyTile) {
                     const int64_t row = kept_row(seg.key0, seg.stride, min(t * kKeyTile + tid, seg.count - 1));
                     l_lds[tid] = lse_bh[row] * kLog2e;
-                    d_lds[tid] = delta_bh[row];
+                    d_lds[tid] = ndelta_bh[row];
                 }
             }
             __syncthreads();
@@ -191,14 +191,14 @@ void bwd_kernel(const BwdParams p) {
                 const float sc = dot_row(x0, ar) * p.scale;                       // scale q.k
                 if (kMode == 0) {
                     const float pr = __builtin_amdgcn_exp2f(sc * kLog2e + seg.log2_mult - my_l);
-                    const float ds = pr * (dot_row(x1, br) - my_d) * p.scale;
+                    const float ds = pr * (dot_row(x1, br) + my_d) * p.scale;
                     axpy_row(ds, ar, acc);                                        // dq += scale ds k
                 } else {
                     const float pr = __builtin_amdgcn_exp2f(sc * kLog2e + seg.log2_mult - l_lds[c]);
                     if (kMode == 1) {
                         axpy_row(pr, br, acc);                                    // dv += P dout
                     } else {
-                        const float ds = pr * (dot_row(x1, br) - d_lds[c]) * p.scale;
+                        const float ds = pr * (dot_row(x1, br) + d_lds[c]) * p.scale;
                         axpy_row(ds, ar, acc);                                    // dk += scale ds q
                     }
                 }
@@ -211,7 +211,7 @@ void bwd_kernel(const BwdParams p) {
 template <typename T>
 hipError_t launch_all(const BwdParams& p, int n_items, int32_t B, hipStream_t st) {
     hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)(((int64_t)p.N * p.H * 16 + 255) / 256), B), dim3(256), 0, st,
-                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.delta, p.lse2, p.H, p.N);
+                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.ndelta, p.lse2, p.H, p.N);
     if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);
     hipLaunchKernelGGL((bwd_kernel<float, 0>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 1>), dim3(n_items), dim3(256), 0, st, p);

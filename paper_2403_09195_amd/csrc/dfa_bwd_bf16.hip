@@ -18,9 +18,9 @@
 //               bf16 result of the first products straight from registers (the register order
 //               of the first product's result is the contraction order sigma fixes).
 // Per 32 walked rows:
-//   dq:  S^T = K~ Q^T, dP^T = V~ dO^T, dS^T = P (dP - delta) scale, dQ^T += K~^T dS^T
-//   dk, dv:  S = Q~ K^T, dP = dO~ V^T, P = exp2(..), dS = P (dP - delta) scale,
-//            dV^T += dO~^T P,  dK^T += Q~^T dS
+//   dq:  S^T = K~ Q^T, dP^T = V~ dO^T, dS^T = P (dP - delta), dQ^T += K~^T dS^T   (times scale at the end)
+//   dk, dv:  S = Q~ K^T, dP - delta = dO~ V^T started from -delta, P = exp2(..), dS = P (dP - delta),
+//            dV^T += dO~^T P,  dK^T += Q~^T dS   (times scale at the end)
 // (~ marks the walked rows).  lse and delta of the walked queries travel with the rows as 4-byte
 // copies.  P is recomputed from lse; there is no online softmax and no rescaling here.
 #include "dfa_device.h"
@@ -98,26 +98,40 @@ __device__ __forceinline__ void pack_block(const float (&x)[16], u32x4 (&pb)[2])
     }
 }
 
-// P and dS of one 32 x 32 block of the dk/dv kernel.  lp / dl: lse (base-2 units) and delta of the walked
-// queries in LDS; register v of a lane is block position 16*(v/8) + 8*g + v%8, lp and dl point at
-// position 8*g.  kBias: the pairs of this step count m times, log2 m = bias (see KeySeg).
+// P and dS of one 32 x 32 block of the dk/dv kernel.  lp: lse (base-2 units) of the walked queries in LDS;
+// register v of a lane is block position 16*(v/8) + 8*g + v%8, lp points at position 8*g.  dpd holds
+// dP - delta already (the accumulators of dP start from -delta).  kBias: the pairs of this step count m
+// times, log2 m = bias (see KeySeg).  The factor scale of dS goes onto the dk accumulator at the end.
 template <bool kBias>
-__device__ __forceinline__ void probs_block(const floatx16& s, const floatx16& dp, const float* lp, const float* dl,
-                                            float c, float scale, float bias, float (&pr)[16], float (&ds)[16]) {
+__device__ __forceinline__ void probs_block(const floatx16& s, const floatx16& dpd, const float* lp,
+                                            float c, float bias, float (&pr)[16], float (&ds)[16]) {
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int e = 0; e < 8; e += 4) {
             const float4 l2 = *reinterpret_cast<const float4*>(lp + 16 * hf + e);
-            const float4 dd = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
-            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w}, dda[4] = {dd.x, dd.y, dd.z, dd.w};
+            const float l2a[4] = {l2.x, l2.y, l2.z, l2.w};
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int v = 8 * hf + e + x;
                 pr[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, kBias ? bias - l2a[x] : -l2a[x]));
-                ds[v] = pr[v] * (dp[v] - dda[x]) * scale;
+                ds[v] = pr[v] * dpd[v];
             }
         }
+}
+
+// -delta of the 32 walked queries of a block as the start value of the dP accumulators: register v of a
+// lane is block position 16*(v/8) + 8*g + v%8, dl points at position 8*g.
+__device__ __forceinline__ floatx16 load_ndelta(const float* dl) {
+    floatx16 r;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int e = 0; e < 8; e += 4) {
+            const float4 d = *reinterpret_cast<const float4*>(dl + 16 * hf + e);
+            r[8 * hf + e] = d.x; r[8 * hf + e + 1] = d.y; r[8 * hf + e + 2] = d.z; r[8 * hf + e + 3] = d.w;
+        }
+    return r;
 }
 
 // dq of a tile: its rows are queries, the lists are walked as keys (K in "A" and "T" layout, V in "A"
@@ -160,7 +174,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
     const uint16_t* const vp = static_cast<const uint16_t*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
     const uint16_t* const gp = static_cast<const uint16_t*>(p.dout) + out_bh * kD;          // row n at n * H * D
     const int64_t g_pitch = (int64_t)p.H * kD;
-    const float* const delta_bh = p.delta + ((int64_t)b * p.H + h) * p.N;
+    const float* const ndelta_bh = p.ndelta + ((int64_t)b * p.H + h) * p.N;
     const float* const lse2_bh = p.lse2 + ((int64_t)b * p.H + h) * p.N;
 
     BwdCopyLane cl;
@@ -203,7 +217,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
 
     // ---- the tile's own rows as B operands (16 d x 32 rows): lane (j, g) holds row j, d 16*kk + 8*g .. +7
     bf16x8 qf[2][4], gf[2][4];           // q and dout of the wave's two 32-row blocks
-    float my_l2[2], my_delta[2];
+    float my_l2[2], my_nd[2];          // lse (base-2 units) and -delta of the wave's rows
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
         const int64_t row = row_idx[wave * 64 + blk * 32 + j];
@@ -213,7 +227,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
             gf[blk][kk] = *reinterpret_cast<const bf16x8*>(gp + row * g_pitch + 16 * kk + 8 * g);
         }
         my_l2[blk] = lse2_bh[row];
-        my_delta[blk] = delta_bh[row];
+        my_nd[blk] = ndelta_bh[row];
     }
     // pin them: the compiler then waits for these loads here and places no vector-memory wait of
     // its own inside the main loop (it cannot see the copies, and its wait would drain them)
@@ -225,7 +239,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
             asm volatile("" : "+v"(gf[blk][kk]));
         }
         asm volatile("" : "+v"(my_l2[blk]));
-        asm volatile("" : "+v"(my_delta[blk]));
+        asm volatile("" : "+v"(my_nd[blk]));
     }
 
     const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, p.scale * kLog2e)));
@@ -283,7 +297,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float pr = __builtin_amdgcn_exp2f(fmaf(s[blk][v], c, -my_l2[blk]));
-                        ds[v] = pr * (dp[blk][v] - my_delta[blk]) * scale;
+                        ds[v] = pr * (dp[blk][v] + my_nd[blk]);    // the factor scale goes onto the accumulator at the end
                     }
                     pack_block(ds, pb[blk]);
                 }
@@ -315,8 +329,8 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    const bf16x4 o = {(__bf16)acc[db][blk][4 * vq], (__bf16)acc[db][blk][4 * vq + 1],
-                                      (__bf16)acc[db][blk][4 * vq + 2], (__bf16)acc[db][blk][4 * vq + 3]};
+                    const bf16x4 o = {(__bf16)(acc[db][blk][4 * vq] * scale), (__bf16)(acc[db][blk][4 * vq + 1] * scale),
+                                      (__bf16)(acc[db][blk][4 * vq + 2] * scale), (__bf16)(acc[db][blk][4 * vq + 3] * scale)};
                     *reinterpret_cast<bf16x4*>(mine + (32 * blk + j) * kPitch + (32 * db + 8 * vq + 4 * g) * 2) = o;
                 }
         // the wave reads back only what it wrote itself; LDS operations of a wave complete in order
@@ -377,7 +391,7 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
     const uint16_t* const vp = static_cast<const uint16_t*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
     const uint16_t* const gp = static_cast<const uint16_t*>(p.dout) + out_bh * kD;          // row n at n * H * D
     const int64_t g_pitch = (int64_t)p.H * kD;
-    const float* const delta_bh = p.delta + ((int64_t)b * p.H + h) * p.N;
+    const float* const ndelta_bh = p.ndelta + ((int64_t)b * p.H + h) * p.N;
     const float* const lse2_bh = p.lse2 + ((int64_t)b * p.H + h) * p.N;
 
     // one 1 KB copy per wave and tensor: wave w fills LDS rows rho = 8w .. 8w+7, lane L lands at row L/8, chunk L%8
@@ -408,7 +422,7 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
         copy16_to_lds(qb, pt * qpitch + t_chunk, st + 2 * kTensorBytes);
         copy16_to_lds(gb, pt * gpitch + t_chunk, st + 3 * kTensorBytes);
         issue_scalars(lse2_bh, c, lane, sc_addr + slot * (kKeyTile * 4));
-        issue_scalars(delta_bh, c, lane, sc_addr + (kBwdStages + slot) * (kKeyTile * 4));
+        issue_scalars(ndelta_bh, c, lane, sc_addr + (kBwdStages + slot) * (kKeyTile * 4));
     };
 
     KeyCursor pf;
@@ -466,22 +480,21 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
                 const int nv = nvalid - 32 * ws;
                 const uint16_t* const qa = t_lds[0][slot] + 32 * ws * kRowElems;
                 const uint16_t* const ga = t_lds[1][slot] + 32 * ws * kRowElems;
-                floatx16 s, dp;
+                floatx16 s, dp = load_ndelta(&sc_lds[1][slot][32 * ws + 8 * g]);   // dp ends up as dP - delta
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qa + (frag_a ^ (16 * kk)));
                     const bf16x8 gf = *reinterpret_cast<const bf16x8*>(ga + (frag_a ^ (16 * kk)));
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kk], kk == 0 ? zero16() : s, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[kk], kk == 0 ? zero16() : dp, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[kk], dp, 0, 0, 0);
                 }
                 if (nv < 32) mask_rows(s, g, nv);
                 // lse and delta of the walked queries: register v is block position 16*(v/8) + 8*g + v%8
                 float pr[16], ds[16];
                 {
                     const float* lp = &sc_lds[0][slot][32 * ws + 8 * g];
-                    const float* dl = &sc_lds[1][slot][32 * ws + 8 * g];
-                    if (cur.bias == 0.f) probs_block<false>(s, dp, lp, dl, c, scale, 0.f, pr, ds);
-                    else probs_block<true>(s, dp, lp, dl, c, scale, cur.bias, pr, ds);
+                    if (cur.bias == 0.f) probs_block<false>(s, dp, lp, c, 0.f, pr, ds);
+                    else probs_block<true>(s, dp, lp, c, cur.bias, pr, ds);
                 }
                 u32x4 pp[2], ps[2];
                 pack_block(pr, pp);
@@ -515,7 +528,8 @@ void bwd_dkdv_bf16_kernel(const BwdParams p) {
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
                     const floatx16& a = which == 0 ? dk_acc[db] : dv_acc[db];
-                    const bf16x4 o = {(__bf16)a[4 * vq], (__bf16)a[4 * vq + 1], (__bf16)a[4 * vq + 2], (__bf16)a[4 * vq + 3]};
+                    const float f = which == 0 ? scale : 1.0f;     // dk = scale dS^T q
+                    const bf16x4 o = {(__bf16)(a[4 * vq] * f), (__bf16)(a[4 * vq + 1] * f), (__bf16)(a[4 * vq + 2] * f), (__bf16)(a[4 * vq + 3] * f)};
                     *reinterpret_cast<bf16x4*>(mine + (32 * which + j) * kPitch + (32 * db + 8 * vq + 4 * g) * 2) = o;
                 }
         // the wave reads back only what it wrote itself; LDS operations of a wave complete in order

@@ -48,7 +48,8 @@ struct BwdParams {
     int64_t skb, skn, skh;
     int64_t svb, svn, svh;
     const float* lse;   // [B, H, N], merged, from the forward pass
-    float* delta;       // [B, H, N] workspace: dout . out per row
+    float* ndelta;      // [B, H, N] workspace: -(dout . out) per row (negated: it is added to dP, in the dk/dv kernel as
+                        // the start value of the dP accumulators)
     float* lse2;        // [B, H, N] workspace: lse * log2(e) per row
     void* dq;
     void* dk;
