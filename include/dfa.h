@@ -128,7 +128,7 @@ int dfa_forward(const void *q, const void *k, const void *v,
  *   dq, dk, dv     device, dtype dt, contiguous [B, N, H, D]; rows kept by no branch get 0
  * dt = DFA_BF16: bf16 operands on the matrix cores, fp32 accumulation, P and dS rounded to bf16
  * before their second products, gradients rounded to bf16.  dt = DFA_F32: fp32 vector arithmetic
- * (correctness path).  Three (bf16) or four (fp32) launches on `stream`; uses the plan cache of dfa_forward.
+ * (correctness path).  Two (bf16) or four (fp32) launches on `stream`; uses the plan cache of dfa_forward.
  */
 int dfa_backward(const void *q, const void *k, const void *v, const void *out, const float *lse,
                  const void *dout, dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,

@@ -9,7 +9,8 @@
 // plan visits a pair once for the m branches that hold it, P carries the factor m (every formula
 // above is linear in P).
 //
-// This file: the per-row preparation both precisions share (delta, and lse in base-2 units) and
+// This file: the per-row preparation of the fp32 path (delta, and lse in base-2 units; the bf16 path does it in
+// its dq kernel) and
 // the fp32 path, correctness-first kernels in fp32 vector arithmetic on the same launch plan as
 // the forward pass, one lane per row of a tile.  bf16 operands go to the matrix-core kernels.  In a
 // segment the kept rows are queries and keys alike, so a tile's key lists are also the lists of
@@ -210,9 +211,9 @@ void bwd_kernel(const BwdParams p) {
 
 template <typename T>
 hipError_t launch_all(const BwdParams& p, int n_items, int32_t B, hipStream_t st) {
+    if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);      // its dq kernel prepares the per-row values itself
     hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)(((int64_t)p.N * p.H * 16 + 255) / 256), B), dim3(256), 0, st,
                        static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.ndelta, p.lse2, p.H, p.N);
-    if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);
     hipLaunchKernelGGL((bwd_kernel<float, 0>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 1>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 2>), dim3(n_items), dim3(256), 0, st, p);

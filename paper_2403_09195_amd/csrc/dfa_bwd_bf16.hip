@@ -5,7 +5,8 @@
 // pair of the definition and delta_n = dout_n . out_n:
 //   dv_j += P dout_n,   ds = P (dout_n . v_j - delta_n),   dq_n += scale ds k_j,   dk_j += scale ds q_n.
 //
-// Two launches on the forward's plan, one for dq and one for dk and dv together; a workgroup owns
+// Two launches on the forward's plan, one for dq (which also leaves -delta and lse in base-2 units of every
+// row in the workspace) and then one for dk and dv together; a workgroup owns
 // a tile of up to 256 rows and walks the tile's lists 64 rows at a time.  In a segment the kept
 // rows are queries and keys alike, so the lists are the tile's keys when its rows act as
 // queries (dq) and the queries that see its rows when they act as keys (dk, dv): no gradient
@@ -174,17 +175,25 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
     const uint16_t* const vp = static_cast<const uint16_t*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
     const uint16_t* const gp = static_cast<const uint16_t*>(p.dout) + out_bh * kD;          // row n at n * H * D
     const int64_t g_pitch = (int64_t)p.H * kD;
-    const float* const ndelta_bh = p.ndelta + ((int64_t)b * p.H + h) * p.N;
-    const float* const lse2_bh = p.lse2 + ((int64_t)b * p.H + h) * p.N;
+    const uint16_t* const op = static_cast<const uint16_t*>(p.out) + out_bh * kD;           // row n at n * H * D
+    const float* const lse_bh = p.lse + ((int64_t)b * p.H + h) * p.N;
+    float* const ndelta_bh = p.ndelta + ((int64_t)b * p.H + h) * p.N;
+    float* const lse2_bh = p.lse2 + ((int64_t)b * p.H + h) * p.N;
 
-    BwdCopyLane cl;
-    {
-        const int rho = 16 * wave + (lane >> 3);                                // LDS row of copy 0 (bit 3 clear)
+    // The lane constants of the copies are worked out afresh at every issue, from a copy of the lane number
+    // the compiler cannot see through: kept across the main loop they are spilled to scratch memory, and the
+    // reloads (vector memory operations the compiler waits for) would drain the copy pipeline every step.
+    auto copy_lane = [&]() {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        BwdCopyLane cl;
+        const int rho = 16 * wave + (ln >> 3);                                  // LDS row of copy 0 (bit 3 clear)
         cl.a_pos = (rho & 0x33) | ((rho & 4) << 1);                             // sigma(rho)
-        cl.a_chunk = 16 * ((lane & 7) ^ k_swizzle(rho));
+        cl.a_chunk = 16 * ((ln & 7) ^ k_swizzle(rho));
         cl.t_pos = rho;
-        cl.t_chunk = 16 * (lane & 7);
-    }
+        cl.t_chunk = 16 * (ln & 7);
+        return cl;
+    };
     // fragment reads: "A" layout row j of a 32-row block, chunk (2*kk + g) ^ swizzle(j); "T" layout as
     // read_v_frag describes
     const int frag_a = j * kRowElems + 8 * (g ^ k_swizzle(j));
@@ -197,6 +206,7 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
 
     auto issue = [&](const KeyCursor& c, int slot) {
         const uint32_t st = t_addr + slot * kStageBytes;
+        const BwdCopyLane cl = copy_lane();
         issue_tensor<true>(kp, p.skn, c, cl, wave, st);
         issue_tensor<true>(vp, p.svn, c, cl, wave, st + kTensorBytes);
         issue_tensor<false>(kp, p.skn, c, cl, wave, st + 2 * kTensorBytes);
@@ -215,9 +225,33 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
         cursor_next(pf, seg_lds, tile.nseg);
     }
 
+    // ---- lse in base-2 units and -delta = -(dout . out) of the wave's rows: worked out here (a lane and its
+    // partner lane ^ 32 hold the two halves of a row) and left in the workspace for the dk/dv kernel, which
+    // reads them for the rows it walks.  Done before the B operands are loaded so that the two do not
+    // need registers at the same time.
+    float my_l2[2], my_nd[2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        const int64_t row = row_idx[wave * 64 + blk * 32 + j];
+        my_l2[blk] = lse_bh[row] * kLog2e;
+        float part = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gp + row * g_pitch + 16 * kk + 8 * g);
+            const bf16x8 ov = *reinterpret_cast<const bf16x8*>(op + row * g_pitch + 16 * kk + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) part = fmaf((float)gv[t], (float)ov[t], part);
+        }
+        my_nd[blk] = -wave_half_sum(part);
+        if (g == 0 && wave * 64 + blk * 32 + j < tile.nrows) {
+            ndelta_bh[row] = my_nd[blk];
+            lse2_bh[row] = my_l2[blk];
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- the tile's own rows as B operands (16 d x 32 rows): lane (j, g) holds row j, d 16*kk + 8*g .. +7
     bf16x8 qf[2][4], gf[2][4];           // q and dout of the wave's two 32-row blocks
-    float my_l2[2], my_nd[2];          // lse (base-2 units) and -delta of the wave's rows
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
         const int64_t row = row_idx[wave * 64 + blk * 32 + j];
@@ -226,8 +260,6 @@ void bwd_dq_bf16_kernel(const BwdParams p) {
             qf[blk][kk] = *reinterpret_cast<const bf16x8*>(qp + row * p.sqn + 16 * kk + 8 * g);
             gf[blk][kk] = *reinterpret_cast<const bf16x8*>(gp + row * g_pitch + 16 * kk + 8 * g);
         }
-        my_l2[blk] = lse2_bh[row];
-        my_nd[blk] = ndelta_bh[row];
     }
     // pin them: the compiler then waits for these loads here and places no vector-memory wait of
     // its own inside the main loop (it cannot see the copies, and its wait would drain them)
