@@ -12,10 +12,13 @@
 // results out), so the tile is as large as LDS allows and the results leave as whole 128-byte
 // lines.
 //
-// Matrix-core mapping (v_mfma_f32_32x32x16_bf16): A operand = 32 weight rows (output
-// features) x 16 k, B operand = 16 k x 32 x-rows.  The result then has one x-row (one row of
-// y) per lane and 4 consecutive output features in 4 consecutive registers.  A wave computes
-// 128 rows x BN/4 features: per 16 k it reads 4 + BN/128 fragments and issues 4 * BN/128 MFMAs.
+// Matrix-core mapping (v_mfma_f32_16x16x32_bf16; lane = 16*g4 + r16): A operand = 16 weight rows (output
+// features) x 32 k, B operand = 32 k x 16 x-rows, each lane supplying 8 consecutive k of row r16.  The result
+// then has one x-row (one row of y) per lane and 4 consecutive output features in its 4 registers.  A wave
+// computes 128 rows x BN/4 features: per 32 k it reads 8 + BN/64 fragments and issues 8 * BN/64 MFMAs.  (The
+// 32x32x16 instruction does the same work in half as many issues but with twice the accumulator traffic
+// per FLOP; under this part's power limit the 16x16x32 form is the faster one: 115 us against 123 us on the
+// QKV projection of the stack workload.)
 // Epilogue: each wave rounds its results to bf16, lays them out row-major in its own piece of
 // LDS (the stages are free by then) and stores them 16 bytes per lane, eight lanes to a row.
 #include "dfa_device.h"
@@ -30,12 +33,13 @@ constexpr int kLinStages = 2;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #define DFA_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-// 16-byte chunk swizzle: chunk c of LDS row rho sits at chunk c ^ swizzle(rho).  Sixteen
-// consecutive rows then spread one chunk column over all 64 banks.
-__device__ __forceinline__ int lin_swizzle(int rho) { return (rho >> 1) & 7; }
+// 16-byte chunk swizzle: chunk c of LDS row rho sits at chunk c ^ swizzle(rho).  Eight consecutive
+// rows then spread one chunk column over all 64 banks (a fragment read takes row r16 of a 16-row block).
+__device__ __forceinline__ int lin_swizzle(int rho) { return rho & 7; }
 
 template <int N>
 __device__ __forceinline__ void lin_wait_vmcnt() {
@@ -68,13 +72,13 @@ template <int BN>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
                         int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n) {
-    constexpr int NB = BN / 128;           // 32-feature blocks per wave
+    constexpr int NT = BN / 64;            // 16-feature blocks per wave
     constexpr uint32_t kXStageBytes = kLinBM * kLinBK * 2, kWStageBytes = BN * kLinBK * 2;
     constexpr uint32_t kXBytes = kLinStages * kXStageBytes;
     __shared__ __attribute__((aligned(1024))) char lds[kXBytes + kLinStages * kWStageBytes];
 
     const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
 
     // tile of this workgroup
     const int die = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
@@ -86,46 +90,40 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
 
     // ---- copies: a copy fills 8 rows of 128 bytes; lane L lands at row L/8, chunk L%8 and fetches
     // the source chunk that the swizzle puts there.  Wave `wave` fills x rows 32*wave .. +31
-    // (4 copies) and w rows (BN/8)*wave .. (BN/64 copies); both starts are multiples of 16, so
-    // the swizzle of row 8u + L/8 of a wave's share is (4*(u & 1) + L/16) & 7.
+    // (4 copies) and w rows (BN/8)*wave .. (BN/64 copies); both starts are multiples of 8, so
+    // the swizzle of row 8u + L/8 of a wave's share is L/8.
     constexpr int kCopies = 4 + BN / 64;   // per wave per stage
     const int r8 = lane >> 3;
-    uint32_t x_off[2], w_off[2];           // byte offset of this lane inside an 8-row group, by parity of the group
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const int chunk = (lane & 7) ^ lin_swizzle(8 * par + r8);
-        x_off[par] = (uint32_t)(r8 * ldx * 2 + 16 * chunk);
-        w_off[par] = (uint32_t)(r8 * ldw * 2 + 16 * chunk);
-    }
+    const int chunk = (lane & 7) ^ lin_swizzle(r8);
+    const uint32_t x_off = (uint32_t)(r8 * ldx * 2 + 16 * chunk);      // byte offset of this lane inside an 8-row group
+    const uint32_t w_off = (uint32_t)(r8 * ldw * 2 + 16 * chunk);
     const uint32_t lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &lds[0]);
 
     auto issue = [&](int ks, int stage) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int row = 32 * wave + 8 * u;
-            lin_copy16(lin_uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off[u & 1],
+            lin_copy16(lin_uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off,
                        lds_addr + stage * kXStageBytes + row * 128);
         }
 #pragma unroll
         for (int u = 0; u < BN / 64; ++u) {
             const int row = (BN / 8) * wave + 8 * u;
-            lin_copy16(lin_uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off[u & 1],
+            lin_copy16(lin_uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off,
                        lds_addr + kXBytes + stage * kWStageBytes + row * 128);
         }
     };
 
     // ---- fragments: lane (j, g) reads row j of a 32-row block, chunk (2*kk + g) ^ swizzle(j)
     const int wm = wave >> 2, wn = wave & 3;
-    const int frag = j * kLinBK + 8 * (g ^ lin_swizzle(j));            // element offset for kk = 0; kk xors 16*kk in
+    const int frag = r16 * kLinBK + 8 * (g4 ^ lin_swizzle(r16));       // element offset for k half 0; half 1 xors 32 in
     const int x_rows = 128 * wm, w_rows = (BN / 4) * wn;               // first row of this wave in the two tiles
 
-    floatx16 acc[NB][4];
+    floatx4 acc[NT][8];                    // [16-feature block][16-row block]: lane (g4, r16), register i = y[row r16][feature 4*g4 + i]
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
+        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int n_k = K / kLinBK;
     issue(0, 0);
@@ -137,27 +135,31 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
         const uint16_t* xs = reinterpret_cast<const uint16_t*>(lds + stage * kXStageBytes) + x_rows * kLinBK;
         const uint16_t* ws = reinterpret_cast<const uint16_t*>(lds + kXBytes + stage * kWStageBytes) + w_rows * kLinBK;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 xf[4], wf[NB];
+        for (int kh = 0; kh < 2; ++kh) {
+            bf16x8 wf[NT];
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-                xf[mb] = *reinterpret_cast<const bf16x8*>(xs + 32 * mb * kLinBK + (frag ^ (16 * kk)));
+            for (int nt = 0; nt < NT; ++nt)
+                wf[nt] = *reinterpret_cast<const bf16x8*>(ws + 16 * nt * kLinBK + (frag ^ (32 * kh)));
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                wf[nb] = *reinterpret_cast<const bf16x8*>(ws + 32 * nb * kLinBK + (frag ^ (16 * kk)));
+            for (int mh = 0; mh < 2; ++mh) {
+                bf16x8 xf[4];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+                for (int m4 = 0; m4 < 4; ++m4)
+                    xf[m4] = *reinterpret_cast<const bf16x8*>(xs + 16 * (4 * mh + m4) * kLinBK + (frag ^ (32 * kh)));
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int m4 = 0; m4 < 4; ++m4)
+                        acc[nt][4 * mh + m4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[m4], acc[nt][4 * mh + m4], 0, 0, 0);
+            }
         }
     }
 
-    // ---- epilogue.  Lane (j, g) holds row x_rows + 32*mb + j of the tile; its registers
-    // 4*vq .. 4*vq+3 of block nb are features w_rows + 32*nb + 8*vq + 4*g .. +3.  Each wave
-    // transposes 64 rows at a time through its own piece of LDS: rows of BN/4 features (64 or
-    // 128 bytes) at a pitch of 16 bytes more, written 8 bytes per lane, read back 16 bytes per
-    // lane with consecutive lanes along a row, and stored as whole rows of the wave's tile.
+    // ---- epilogue.  Lane (g4, r16) holds row x_rows + 16*mt + r16 of the tile; its registers 0..3 of
+    // block nt are features w_rows + 16*nt + 4*g4 .. +3.  Each wave transposes 64 rows at a time through
+    // its own piece of LDS: rows of BN/4 features (64 or 128 bytes) at a pitch of 16 bytes more, written 8
+    // bytes per lane, read back 16 bytes per lane with consecutive lanes along a row, and stored as whole
+    // rows of the wave's tile.
     __syncthreads();               // every wave is done with the stages
     constexpr int kRowBytes = (BN / 4) * 2, kPitch = kRowBytes + 16, kLanesPerRow = kRowBytes / 16;
     constexpr int kRowsPerStore = 64 / kLanesPerRow;
@@ -166,15 +168,13 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
 #pragma unroll
-        for (int mbl = 0; mbl < 2; ++mbl)
+        for (int m4 = 0; m4 < 4; ++m4)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const floatx16& a = acc[nb][2 * half + mbl];
-                    const bf16x4 o = {(__bf16)a[4 * vq], (__bf16)a[4 * vq + 1], (__bf16)a[4 * vq + 2], (__bf16)a[4 * vq + 3]};
-                    *reinterpret_cast<bf16x4*>(mine + (32 * mbl + j) * kPitch + (32 * nb + 8 * vq + 4 * g) * 2) = o;
-                }
+            for (int nt = 0; nt < NT; ++nt) {
+                const floatx4& a = acc[nt][4 * half + m4];
+                const bf16x4 o = {(__bf16)a[0], (__bf16)a[1], (__bf16)a[2], (__bf16)a[3]};
+                *reinterpret_cast<bf16x4*>(mine + (16 * m4 + r16) * kPitch + (16 * nt + 4 * g4) * 2) = o;
+            }
         // the wave reads only what it wrote itself: LDS operations of a wave complete in order
 #pragma unroll
         for (int s = 0; s < 64 / kRowsPerStore; ++s) {
