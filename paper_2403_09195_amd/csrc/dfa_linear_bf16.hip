@@ -30,6 +30,7 @@ namespace {
 constexpr int kLinBM = 256;                // rows of y per workgroup
 constexpr int kLinBK = 64;                 // k elements per stage: one 128-byte LDS row
 constexpr int kLinStages = 2;
+constexpr int kLinCusPerDie = 32;          // one workgroup fits a CU at a time
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -64,29 +65,18 @@ __device__ __forceinline__ const void* lin_uniform_ptr(const void* p) {
     return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
 }
 
-// y[m][n] = sum_k x[m][k] * w[n][k].  Requires M % 256 == 0, N % BN == 0, K % 64 == 0, every
-// row of x, w and y starting on a 16-byte boundary.  grid = (M/256) * (N/BN) workgroups,
-// workgroup i on die i % 8; tiles are dealt so that one die walks all feature tiles of a row
-// band before moving on (the x band is then read from memory once per die, w stays in its L2).
+// The 256 x BN tile of y at (m0, n0): y[m][n] = sum_k x[m][k] * w[n][k].  lds: the workgroup's LDS (two stages
+// of a 256-row x tile and a BN-row w tile).
 template <int BN>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
-                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n) {
+__device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                            uint16_t* __restrict__ y, int K, int64_t ldx, int64_t ldw, int64_t ldy,
+                                            int64_t m0, int64_t n0, char* lds) {
     constexpr int NT = BN / 64;            // 16-feature blocks per wave
     constexpr uint32_t kXStageBytes = kLinBM * kLinBK * 2, kWStageBytes = BN * kLinBK * 2;
     constexpr uint32_t kXBytes = kLinStages * kXStageBytes;
-    __shared__ __attribute__((aligned(1024))) char lds[kXBytes + kLinStages * kWStageBytes];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
-
-    // tile of this workgroup
-    const int die = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
-    const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;   // tiles are numbered band by band
-    const int t = die * per_die + local;
-    if (t >= tiles_m * tiles_n) return;
-    const int tm = t / tiles_n, tn = t % tiles_n;
-    const int64_t m0 = (int64_t)tm * kLinBM, n0 = (int64_t)tn * BN;
 
     // ---- copies: a copy fills 8 rows of 128 bytes; lane L lands at row L/8, chunk L%8 and fetches
     // the source chunk that the swizzle puts there.  Wave `wave` fills x rows 32*wave .. +31
@@ -186,14 +176,40 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
     }
 }
 
+// Requires M % 256 == 0, N % BN == 0, K % 64 == 0, every row of x, w and y starting on a 16-byte boundary.
+// Workgroup i runs on die i % 8; tiles (256 x BN) are numbered band by band and dealt so that one die walks all
+// feature tiles of a row band before moving on (the x band is then read from memory once per die, w stays
+// in its L2).  One workgroup fits a CU at a time, so a die works its share off in rounds of 32 tiles; when
+// the last round of a die would be at most half full (wide tiles only), its tiles are cut into two
+// 128-feature halves, which fill the die for a round half as long: the first `wide_per_die` workgroups of a
+// die take whole tiles, the others halves.
+template <int BN>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
+                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n, int wide_per_die) {
+    __shared__ __attribute__((aligned(1024))) char lds[kLinStages * (kLinBM + BN) * kLinBK * 2];
+    const int die = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
+    const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;
+    const bool whole = BN == 128 || local < wide_per_die;
+    const int t = die * per_die + (whole ? local : wide_per_die + (local - wide_per_die) / 2);
+    if (t >= tiles_m * tiles_n || (!whole && wide_per_die + (local - wide_per_die) / 2 >= per_die)) return;
+    const int64_t m0 = (int64_t)(t / tiles_n) * kLinBM, n0 = (int64_t)(t % tiles_n) * BN;
+    if (whole) linear_tile<BN>(x, w, y, K, ldx, ldw, ldy, m0, n0, lds);
+    else linear_tile<128>(x, w, y, K, ldx, ldw, ldy, m0, n0 + 128 * ((local - wide_per_die) & 1), lds);
+}
+
 template <int BN>
 hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                         int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st) {
     const int tiles_m = (int)(M / kLinBM), tiles_n = N / BN;
     const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;
-    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(per_die * kNumXcd), dim3(512), 0, st,
+    // wide tiles: whole rounds of a die's 32 CUs as they are, a last round that is at most half full in halves
+    const int rem = per_die % kLinCusPerDie;
+    const int wide_per_die = (BN == 256 && rem > 0 && 2 * rem <= kLinCusPerDie) ? per_die - rem : per_die;
+    const int wg_per_die = wide_per_die + 2 * (per_die - wide_per_die);
+    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(wg_per_die * kNumXcd), dim3(512), 0, st,
                        static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(y),
-                       K, ldx, ldw, ldy, tiles_m, tiles_n);
+                       K, ldx, ldw, ldy, tiles_m, tiles_n, wide_per_die);
     return hipGetLastError();
 }
 

@@ -32,9 +32,11 @@ def _linear_bar(x_exact, w_exact, y_ref):
     return 2.0 ** -8 * np.abs(y_ref) + K * 2.0 ** -24 * mag + 1e-30
 
 
-# (36864, 1024) is large enough for the 256-feature tile to be chosen; the others run the 128-feature tile
+# (36864, 1024) is large enough for the 256-feature tile to be chosen; (28672, 2048) has 112 such tiles per die,
+# three full rounds and a half-full one, whose 16 tiles are cut into 128-feature halves; the others run the
+# 128-feature tile throughout
 @pytest.mark.parametrize("M,N,K", [(256, 128, 64), (512, 256, 128), (768, 384, 192), (1024, 2304, 768), (512, 768, 768),
-                                   (36864, 1024, 128)])
+                                   (36864, 1024, 128), (28672, 2048, 64)])
 def test_linear_against_fp64_matmul(B, oracle, M, N, K):
     x, xe = _bf16(401, 3, (M, K))
     w, we = _bf16(401, 10, (N, K), std=0.02)
