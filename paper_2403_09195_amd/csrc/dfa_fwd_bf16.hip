@@ -36,7 +36,8 @@
 // the MFMAs of the NEXT block's scores and of the PREVIOUS block's accumulation while its
 // vector ALU turns the CURRENT block's scores into probabilities, all in one hand-ordered
 // instruction stream (see beat()), so matrix cores and vector ALU overlap inside each wave
-// and not only between the two waves that share a SIMD.
+// and not only between the two waves that share a SIMD.  The first beat of a walk (nothing to
+// accumulate yet) and the last (nothing left to score) stand outside the loop in trimmed form.
 #include "dfa_device.h"
 #include "dfa_mfma.h"
 
@@ -185,6 +186,10 @@ __device__ __forceinline__ void accumulate_block(const uint16_t* vblk, const Fra
 // row-sum instructions of three different score pairs (a vector instruction that needs the
 // result of the one just before it stalls the wave, so each pair moves one stage per slot).
 // Scheduling fences keep the compiler from regrouping the slots.
+// kScores / kAccumulate: the beat has a next block to score / a previous block to accumulate (the first
+// beat of a walk has no previous block, the last one no next block; their MFMAs and fragment reads are
+// left out).
+template <bool kScores, bool kAccumulate>
 __device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_prev, const FragLane& fl,
                                      const bf16x8 (&qf)[2][4], const floatx16 (&s_cur)[2], floatx16 (&s_next)[2],
                                      const u32x4 (&p_prev)[2][2], u32x4 (&p_cur)[2][2], floatx16 (&oacc)[2][2],
@@ -194,17 +199,19 @@ __device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_p
     float a[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // two independent partial row sums per query block
 
     auto load_group = [&](int r) {     // group r: d-step r of the scores, (d block r/2, 16-key step r%2) of the accumulation
-        kf[r & 1] = *reinterpret_cast<const bf16x8*>(k_next + (fl.k ^ (16 * r)));
-        vf[r & 1] = read_v_frag(v_prev + fl.v + 16 * (r & 1) * kRowElems + 32 * (r >> 1));
+        if (kScores) kf[r & 1] = *reinterpret_cast<const bf16x8*>(k_next + (fl.k ^ (16 * r)));
+        if (kAccumulate) vf[r & 1] = read_v_frag(v_prev + fl.v + 16 * (r & 1) * kRowElems + 32 * (r >> 1));
     };
     auto mfma = [&](int k) {           // MFMA k of the beat: group r = k/4; scores for query block 0, 1, then accumulation for 0, 1
         const int r = k >> 2, qb = k & 1;
         if ((k & 2) == 0) {
+            if (!kScores) return;
             floatx16 z;
 #pragma unroll
             for (int v = 0; v < 16; ++v) z[v] = 0.f;
             s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[r & 1], qf[qb][r], r == 0 ? z : s_next[qb], 0, 0, 0);
         } else {
+            if (!kAccumulate) return;
             const int db = r >> 1, st = r & 1;
             oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r & 1], __builtin_bit_cast(bf16x8, p_prev[qb][st]), oacc[db][qb], 0, 0, 0);
         }
@@ -329,15 +336,21 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     const uint16_t* const kp = static_cast<const uint16_t*>(p.k) + (int64_t)b * p.skb + (int64_t)h * p.skh;
     const uint16_t* const vp = static_cast<const uint16_t*>(p.v) + (int64_t)b * p.svb + (int64_t)h * p.svh;
 
-    // what this lane fetches in each copy (see CopyLane)
-    CopyLane cl;
-    {
-        const int rho = 16 * wave + (lane >> 3);                                // LDS row of copy 0 (bit 3 clear)
+    // What this lane fetches in each copy (see CopyLane): worked out afresh at every issue, from a copy of the
+    // lane number the compiler cannot see through.  Kept across the main loop these four values are spilled
+    // to scratch memory, and their reloads (vector memory operations the compiler waits for) would drain
+    // the copy pipeline every step.
+    auto copy_lane = [&]() {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        CopyLane cl;
+        const int rho = 16 * wave + (ln >> 3);                                  // LDS row of copy 0 (bit 3 clear)
         cl.kpos = (rho & 0x33) | ((rho & 4) << 1);                              // sigma(rho)
-        cl.kchunk = 16 * ((lane & 7) ^ k_swizzle(rho));
+        cl.kchunk = 16 * ((ln & 7) ^ k_swizzle(rho));
         cl.vpos = rho;
-        cl.vchunk = 16 * (lane & 7);
-    }
+        cl.vchunk = 16 * (ln & 7);
+        return cl;
+    };
 
     // what this lane reads back as MFMA fragments
     auto frag_lane = [](int ln) {
@@ -383,7 +396,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
     for (int s = 0; s <= 2; ++s)
         if (s < n_steps) {
-            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + s * kStageBytes, v_lds_addr + s * kStageBytes);
+            issue_stage(p, kp, vp, pf, copy_lane(), wave, k_lds_addr + s * kStageBytes, v_lds_addr + s * kStageBytes);
             cursor_next(pf, seg_lds, tile.nseg);
         }
 
@@ -421,51 +434,62 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
 
-    // Software pipeline over 32-key blocks (two per stage).  Entering trip s: s_a holds the
-    // scores of block 2s, p_b the probabilities of block 2s-1 (zero before the first block).
+    // Software pipeline over 32-key blocks (two per stage).  Block 2s of step s is turned into probabilities in
+    // beat A(s), block 2s+1 in beat B(s); A(s) also scores block 2s+1 and accumulates block 2s-1, B(s) scores
+    // block 2s+2 and accumulates block 2s.  The first A has nothing to accumulate and the last B nothing to
+    // score, so both stand outside the loop, whose trip s runs B(s) and A(s+1).
     floatx16 s_a[2], s_b[2];
     u32x4 p_a[2][2], p_b[2][2];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int st = 0; st < 2; ++st) p_b[qb][st] = u32x4{0u, 0u, 0u, 0u};
-    if (wave_live) scores_block(k_lds[0], fl, qf, s_a);
-
+    float psum[2];
     int stage = 0;
-    for (int s = 0; s < n_steps; ++s) {
-        const int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+    int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+    // a progression whose keys count m times: log2 m comes off the reference exponents held in m_ref
+    auto enter_step = [&]() {
+        nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
         if (cur.bias != bias_cur) {            // both blocks of this step still hold raw scores
             m_ref[0] -= cur.bias - bias_cur;
             m_ref[1] -= cur.bias - bias_cur;
             bias_cur = cur.bias;
         }
+    };
+    enter_step();
+    if (wave_live) {
+        scores_block(k_lds[0], fl, qf, s_a);
+        if (nvalid < 32) mask_block(s_a, g, nvalid);
+        beat<true, false>(k_lds[0] + 32 * kRowElems, v_lds[0], fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
+        settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
+    }
+    for (int s = 0; s + 1 < n_steps; ++s) {
         const int stage_prev = stage == 0 ? kStages - 1 : stage - 1;
         const int stage_next = stage == kStages - 1 ? 0 : stage + 1;
-        float psum[2];
-        if (wave_live) {
-            // beat 2s: scores of block 2s+1, accumulation of block 2s-1 (before the first block:
-            // zero probabilities against rows that are in LDS anyway), numerators of block 2s
-            if (nvalid < 32) mask_block(s_a, g, nvalid);
-            const uint16_t* v_prev = (s == 0 ? v_lds[0] : v_lds[stage_prev]) + 32 * kRowElems;
-            beat(k_lds[stage] + 32 * kRowElems, v_prev, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
-            settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
-        }
         // stage s+1 has landed once at most the 4 copies of stage s+2 are still outstanding
         if (s + 2 < n_steps) wait_vmcnt<4>(); else wait_vmcnt<0>();
         __syncthreads();       // every wave's share of stage s+1 is in LDS, and everyone is done with stage s-1
         if (s + 3 < n_steps) {
-            issue_stage(p, kp, vp, pf, cl, wave, k_lds_addr + stage_prev * kStageBytes, v_lds_addr + stage_prev * kStageBytes);
+            issue_stage(p, kp, vp, pf, copy_lane(), wave, k_lds_addr + stage_prev * kStageBytes, v_lds_addr + stage_prev * kStageBytes);
             cursor_next(pf, seg_lds, tile.nseg);
         }
         if (wave_live) {
-            // beat 2s+1: scores of block 2s+2 (past the last block: of whatever the next stage
-            // holds, never used), accumulation of block 2s, numerators of block 2s+1
+            // B(s): scores of block 2s+2, accumulation of block 2s, numerators of block 2s+1
             if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
-            beat(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
+            beat<true, true>(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
             settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
         }
         cursor_next(cur, seg_lds, tile.nseg);
+        enter_step();
+        if (wave_live) {
+            // A(s+1): scores of block 2s+3, accumulation of block 2s+1, numerators of block 2s+2
+            if (nvalid < 32) mask_block(s_a, g, nvalid);
+            beat<true, true>(k_lds[stage_next] + 32 * kRowElems, v_lds[stage] + 32 * kRowElems, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
+            settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
+        }
         stage = stage_next;
+    }
+    if (wave_live) {
+        // B of the last step: accumulation of its first block, numerators of its second
+        if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
+        beat<false, true>(k_lds[stage], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
+        settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
     }
     // From here on the lane constants are worked out afresh, from a copy of the lane number the
     // compiler cannot see through: carried across the loop they would cost it registers that
@@ -474,8 +498,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     asm volatile("" : "+v"(lane_e));
     // accumulation of the last block
     if (wave_live) {
-        const int stage_last = stage == 0 ? kStages - 1 : stage - 1;
-        accumulate_block(v_lds[stage_last] + 32 * kRowElems, frag_lane(lane_e), p_b, oacc);
+        accumulate_block(v_lds[stage] + 32 * kRowElems, frag_lane(lane_e), p_b, oacc);
     }
 
     // ---- epilogue: normalise, log-sum-exp, place each row at its own token (Eq. 3)
