@@ -21,7 +21,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
 WORKLOAD = "throughput"
 # HBM bytes per launch of the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
 # the copy-kernel calibration (profiles/dfa_fwd_bf16_throughput.md); None for other workloads
-MEASURED_HBM_TRAFFIC_BYTES = {"throughput": 567457183}
+MEASURED_HBM_TRAFFIC_BYTES = {"throughput": 557848500}
 
 
 HBM_PEAK_GBS = 8000.0               # MI355X HBM3E (published)

@@ -38,6 +38,16 @@
 // instruction stream (see beat()), so matrix cores and vector ALU overlap inside each wave
 // and not only between the two waves that share a SIMD.  The first beat of a walk (nothing to
 // accumulate yet) and the last (nothing left to score) stand outside the loop in trimmed form.
+//
+// Row sums: the vector ALU's issue slots are what a beat runs out of first (an exponent, an exponential
+// and half a rounding per score already fill the time of the MFMAs beside them), so the softmax
+// denominators are not added up there.  The rounded probabilities sit in registers as B operands of the
+// second product; one more small MFMA per 16-key group (v_mfma_f32_16x16x32_bf16 against a constant 0/1
+// selector, see `sel` in the kernel) sums them per query on the matrix cores, which have time to spare.
+// The denominator is therefore the sum of the bf16-rounded numerators, the same values the accumulator
+// is built from: out is their exact weighted mean, and lse carries their rounding (each numerator is off
+// by at most 2^-9 relative on average and 2^-8 at worst, so |error of lse| <= 2^-8 when one key dominates
+// and far less when many keys share the weight).
 #include "dfa_device.h"
 #include "dfa_mfma.h"
 
@@ -45,6 +55,7 @@ namespace dfa {
 
 namespace {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kStages = 4;                 // 64-key K/V stages in LDS
 
 // Per-lane constants of the global->LDS copies.  A wave issues 2 K copies and 2 V copies per
@@ -83,9 +94,10 @@ constexpr float kRebaseThreshold = 256.0f;
 
 // Softmax numerators of one 32-key block against the current reference exponents m_ref (no
 // row maximum is taken here): p = exp2(c*s - m_ref), rounded to bf16 (nearest even) and packed
-// straight into the B operands of the second product; psum = this lane's share of the row
-// sums, in fp32 over the unrounded values.  Plain form, used after a rebase; beat() does the
-// same arithmetic in its hand-ordered stream.
+// straight into the B operands of the second product; psum = the row sums of the block (whole rows:
+// both lanes that share a query hold the same value), in fp32 over the unrounded values.  Plain form,
+// used after a rebase; beat() takes the numerators the same way in its hand-ordered stream and has
+// the matrix cores add them up.
 __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const float (&m_ref)[2],
                                           u32x4 (&pb)[2][2], float (&psum)[2]) {
 #pragma unroll
@@ -100,7 +112,7 @@ __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const
             a0 += e0;
             a1 += e1;
         }
-        psum[qb] = a0 + a1;
+        psum[qb] = wave_half_sum(a0 + a1);
     }
 }
 
@@ -181,10 +193,12 @@ __device__ __forceinline__ void accumulate_block(const uint16_t* vblk, const Fra
 // same time from within a single wave:
 //   matrix cores : S^T of the NEXT block (K at k_next -> s_next), and O^T += V~^T P^T of the
 //                  PREVIOUS block (V at v_prev, probabilities p_prev);
-//   vector ALU   : softmax numerators of the CURRENT block (s_cur -> p_cur, psum).
-// The stream is laid out slot by slot: one MFMA, then the exponent, exponential and rounding /
-// row-sum instructions of three different score pairs (a vector instruction that needs the
+//   vector ALU   : softmax numerators of the CURRENT block (s_cur -> p_cur).
+// The stream is laid out slot by slot: one MFMA, then the exponent, exponential and rounding
+// instructions of three different score pairs (a vector instruction that needs the
 // result of the one just before it stalls the wave, so each pair moves one stage per slot).
+// Whenever a 16-key group of p_cur is complete, one row-sum MFMA (selector `sel` times that group)
+// adds it to psum: register 0 of its result is the sum over the group's 16 keys of the lane's query.
 // Scheduling fences keep the compiler from regrouping the slots.
 // kScores / kAccumulate: the beat has a next block to score / a previous block to accumulate (the first
 // beat of a walk has no previous block, the last one no next block; their MFMAs and fragment reads are
@@ -193,10 +207,10 @@ template <bool kScores, bool kAccumulate>
 __device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_prev, const FragLane& fl,
                                      const bf16x8 (&qf)[2][4], const floatx16 (&s_cur)[2], floatx16 (&s_next)[2],
                                      const u32x4 (&p_prev)[2][2], u32x4 (&p_cur)[2][2], floatx16 (&oacc)[2][2],
-                                     float c, const float (&m_ref)[2], float (&psum)[2]) {
+                                     float c, const float (&m_ref)[2], float (&psum)[2], const bf16x8& sel) {
     bf16x8 kf[2], vf[2];           // fragments of MFMA group r live in slot r & 1
     float t[16][2];                // exponents, then exponentials, of score pair q
-    float a[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // two independent partial row sums per query block
+    floatx4 rs[2];                 // row sums of the rounded numerators, from the matrix cores (register 0)
 
     auto load_group = [&](int r) {     // group r: d-step r of the scores, (d block r/2, 16-key step r%2) of the accumulation
         if (kScores) kf[r & 1] = *reinterpret_cast<const bf16x8*>(k_next + (fl.k ^ (16 * r)));
@@ -236,13 +250,17 @@ __device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_p
             const int q = m - 2, qb = q >> 3, pr = q & 7;
             const bf16x2 w = {(__bf16)t[q][0], (__bf16)t[q][1]};
             p_cur[qb][pr >> 2][pr & 3] = __builtin_bit_cast(uint32_t, w);
-            a[qb][0] += t[q][0];
-            a[qb][1] += t[q][1];
+        }
+        if (m == 7 || m == 11 || m == 15) {             // row sums of the 16-key group finished two slots ago
+            const int grp = (m - 7) >> 2, qb = grp >> 1, st = grp & 1;
+            rs[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, __builtin_bit_cast(bf16x8, p_cur[qb][st]),
+                                                             st == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : rs[qb], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    psum[0] = a[0][0] + a[0][1];
-    psum[1] = a[1][0] + a[1][1];
+    rs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, __builtin_bit_cast(bf16x8, p_cur[1][1]), rs[1], 0, 0, 0);
+    psum[0] = rs[0][0];
+    psum[1] = rs[1][0];
 }
 
 // The wave-uniform end of a beat: accept the numerators, or (rarely) move the reference
@@ -429,7 +447,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // m_ref as (reference exponent - log2 m of the progression being walked) and moving it when the
     // walk enters a progression of another multiplicity; sums and accumulator stay on the true reference.
     float m_ref[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};               // this lane's share of the running sum
+    float l_run[2] = {0.f, 0.f};               // running sum of the row (the two lanes of a query hold the same value)
     float bias_cur = 0.f;                      // log2 m held in m_ref (wave-uniform)
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
@@ -438,6 +456,21 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // beat A(s), block 2s+1 in beat B(s); A(s) also scores block 2s+1 and accumulates block 2s-1, B(s) scores
     // block 2s+2 and accumulates block 2s.  The first A has nothing to accumulate and the last B nothing to
     // score, so both stand outside the loop, whose trip s runs B(s) and A(s+1).
+    // A operand of the row-sum products (v_mfma_f32_16x16x32_bf16 on a B operand of the second product, lane =
+    // 16*g4 + n): that instruction reads lane (n, g4) as contraction slots 8*g4 .. +7 of column n, so column n
+    // gathers the 8 keys each of lanes n, 16+n, 32+n, 48+n, which are query n of the block (slots 0-7 and
+    // 16-23) and query 16+n (slots 8-15 and 24-31).  Result row 4*g4 goes to register 0 of lane group g4:
+    // rows 0 and 8 select the slots of query n, rows 4 and 12 those of query 16+n, all other rows are zero,
+    // so register 0 of every lane receives the sum over all 16 keys of its own query.  (An infinite
+    // numerator of one query turns its neighbour's sum into NaN through a zero of the selector; either
+    // fails the test in settle(), which then redoes the block without the matrix cores.)
+    bf16x8 sel;
+    {
+        const int mrow = lane & 15, g4 = lane >> 4;
+        const bool on = (mrow & 3) == 0 && ((mrow >> 2) & 1) == (g4 & 1);
+        const uint32_t w = on ? 0x3f803f80u : 0u;
+        sel = __builtin_bit_cast(bf16x8, u32x4{w, w, w, w});
+    }
     floatx16 s_a[2], s_b[2];
     u32x4 p_a[2][2], p_b[2][2];
     float psum[2];
@@ -456,7 +489,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     if (wave_live) {
         scores_block(k_lds[0], fl, qf, s_a);
         if (nvalid < 32) mask_block(s_a, g, nvalid);
-        beat<true, false>(k_lds[0] + 32 * kRowElems, v_lds[0], fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
+        beat<true, false>(k_lds[0] + 32 * kRowElems, v_lds[0], fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum, sel);
         settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
     }
     for (int s = 0; s + 1 < n_steps; ++s) {
@@ -472,7 +505,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         if (wave_live) {
             // B(s): scores of block 2s+2, accumulation of block 2s, numerators of block 2s+1
             if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
-            beat<true, true>(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
+            beat<true, true>(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum, sel);
             settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
         }
         cursor_next(cur, seg_lds, tile.nseg);
@@ -480,7 +513,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         if (wave_live) {
             // A(s+1): scores of block 2s+3, accumulation of block 2s+1, numerators of block 2s+2
             if (nvalid < 32) mask_block(s_a, g, nvalid);
-            beat<true, true>(k_lds[stage_next] + 32 * kRowElems, v_lds[stage] + 32 * kRowElems, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum);
+            beat<true, true>(k_lds[stage_next] + 32 * kRowElems, v_lds[stage] + 32 * kRowElems, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum, sel);
             settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
         }
         stage = stage_next;
@@ -488,7 +521,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     if (wave_live) {
         // B of the last step: accumulation of its first block, numerators of its second
         if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
-        beat<false, true>(k_lds[stage], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum);
+        beat<false, true>(k_lds[stage], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum, sel);
         settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
     }
     // From here on the lane constants are worked out afresh, from a copy of the lane number the
@@ -507,7 +540,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int slot = wave * 64 + qb * 32 + j_e;
-        const float l_tot = wave_half_sum(l_run[qb]);
+        const float l_tot = l_run[qb];
         inv[qb] = 1.0f / l_tot;
         if (lse_out && g_e == 0 && slot < tile.nrows)
             lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;

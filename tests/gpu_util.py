@@ -25,6 +25,16 @@ def error_stats(got, ref):
     return float(d.max()), float(d.mean())
 
 
+# lse of the bf16 path.  The workload definition gives no bar for it; this one follows from the arithmetic: the
+# kernel's denominator is the sum of the numerators after their rounding to bf16 (the values the second
+# product uses, added up on the matrix cores), each off by at most 2^-8 relative (half a unit of an 8-bit
+# significand), so the sum is off by at most 2^-8 relative and lse by -ln(1 - 2^-8) = 3.914e-3, reached only
+# when a single key carries the row and sits badly between two bf16 values; rows whose weight is spread over
+# many keys see the roundings average out (3e-4 at the throughput workload).  The rest of the bar covers the
+# fp32 rounding of lse itself.
+BF16_LSE = 3.95e-3
+
+
 def check_lse(got, ref, atol, rtol=0.0):
     """-inf must match exactly; finite values within atol + rtol*|ref|."""
     inf_ref = np.isneginf(ref)

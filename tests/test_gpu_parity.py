@@ -1,11 +1,12 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
 seeded inputs.  Bars: index maps and byte movement bit-exact; bf16 outputs max-abs <= 2e-2 and
 mean-abs <= 2e-3; fp32 outputs max-abs <= 1e-5; lse (no bar given by the workload definition)
-<= 2e-3 for bf16 and 1e-5 * max(1, |lse|) for fp32, with -inf matching exactly."""
+<= 3.95e-3 for bf16 (derived in gpu_util.BF16_LSE) and 1e-5 * max(1, |lse|) for fp32, with -inf matching
+exactly."""
 import numpy as np
 import pytest
 
-from gpu_util import check_lse, error_stats, make_qkv, to_device, to_f64
+from gpu_util import BF16_LSE, check_lse, error_stats, make_qkv, to_device, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -23,7 +24,7 @@ def B():
 
 def _check_bf16(out, lse, o_ref, l_ref, tag=""):
     mx, mean = error_stats(to_f64(out), o_ref)
-    le = check_lse(to_f64(lse), l_ref, atol=2e-3)
+    le = check_lse(to_f64(lse), l_ref, atol=BF16_LSE)
     print(f"[{tag}] bf16 out max-abs {mx:.3e} mean-abs {mean:.3e} lse max-abs {le:.3e}", flush=True)
     assert mx <= BF16_MAX and mean <= BF16_MEAN
     return mx, mean
@@ -349,7 +350,7 @@ def test_bf16_full_size_configs_on_sampled_rows(B, oracle, name, n_samples):
     mx, mean = error_stats(got_o, o_ref)
     le = float(np.abs(got_l - l_ref).max())
     print(f"[{name}] sampled {n_samples} rows: out max-abs {mx:.3e} mean-abs {mean:.3e} lse {le:.3e}", flush=True)
-    assert mx <= BF16_MAX and mean <= BF16_MEAN and le <= 2e-3
+    assert mx <= BF16_MAX and mean <= BF16_MEAN and le <= BF16_LSE
 
 
 # ---------------------------------------------------------------- stage entry points
@@ -365,7 +366,7 @@ def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
         ob, lb = B.forward_branch(q, k, v, w, r, 0.125)
         assert ob.dtype == torch.float32
         mx, mean = error_stats(to_f64(ob), bo_ref[x])
-        check_lse(to_f64(lb), bl_ref[x], atol=2e-3 if dtype == "bf16" else 1e-5, rtol=0 if dtype == "bf16" else 1e-5)
+        check_lse(to_f64(lb), bl_ref[x], atol=BF16_LSE if dtype == "bf16" else 1e-5, rtol=0 if dtype == "bf16" else 1e-5)
         assert mx <= (BF16_MAX if dtype == "bf16" else F32_MAX)
         dead = np.isneginf(bl_ref[x]).transpose(0, 2, 1)
         assert np.all(to_f64(ob)[dead] == 0.0)
