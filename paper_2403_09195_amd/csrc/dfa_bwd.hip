@@ -26,22 +26,11 @@ template <typename T>
 __device__ __forceinline__ float4 load4(const T* p);
 template <>
 __device__ __forceinline__ float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
-template <>
-__device__ __forceinline__ float4 load4<uint16_t>(const uint16_t* p) {
-    const uint2 b = *reinterpret_cast<const uint2*>(p);          // four bf16: widen by shifting into the high half
-    return make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xffff0000u),
-                       __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xffff0000u));
-}
 template <typename T>
 __device__ __forceinline__ void store4v(T* p, float a, float b, float c, float d);
 template <>
 __device__ __forceinline__ void store4v<float>(float* p, float a, float b, float c, float d) {
     *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
-}
-template <>
-__device__ __forceinline__ void store4v<uint16_t>(uint16_t* p, float a, float b, float c, float d) {
-    const bf16x4 o = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};   // round to nearest even
-    *reinterpret_cast<bf16x4*>(p) = o;
 }
 
 template <typename T>
@@ -209,21 +198,18 @@ void bwd_kernel(const BwdParams p) {
     if (live) store_row<T>(grad, acc);
 }
 
-template <typename T>
-hipError_t launch_all(const BwdParams& p, int n_items, int32_t B, hipStream_t st) {
-    if (sizeof(T) == 2) return launch_bwd_bf16(p, n_items, st);      // its dq kernel prepares the per-row values itself
-    hipLaunchKernelGGL((bwd_delta_kernel<T>), dim3((unsigned)(((int64_t)p.N * p.H * 16 + 255) / 256), B), dim3(256), 0, st,
-                       static_cast<const T*>(p.out), static_cast<const T*>(p.dout), p.lse, p.ndelta, p.lse2, p.H, p.N);
+}  // namespace
+
+// fp32 operands: the per-row preparation, then one vector kernel per gradient.  bf16 operands go to the
+// matrix-core kernels, whose dq kernel prepares the per-row values itself.
+hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st) {
+    if (bf16) return launch_bwd_bf16(p, n_items, st);
+    hipLaunchKernelGGL((bwd_delta_kernel<float>), dim3((unsigned)(((int64_t)p.N * p.H * 16 + 255) / 256), B), dim3(256), 0, st,
+                       static_cast<const float*>(p.out), static_cast<const float*>(p.dout), p.lse, p.ndelta, p.lse2, p.H, p.N);
     hipLaunchKernelGGL((bwd_kernel<float, 0>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 1>), dim3(n_items), dim3(256), 0, st, p);
     hipLaunchKernelGGL((bwd_kernel<float, 2>), dim3(n_items), dim3(256), 0, st, p);
     return hipGetLastError();
-}
-
-}  // namespace
-
-hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st) {
-    return bf16 ? launch_all<uint16_t>(p, n_items, B, st) : launch_all<float>(p, n_items, B, st);
 }
 
 }  // namespace dfa

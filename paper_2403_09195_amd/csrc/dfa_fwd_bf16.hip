@@ -278,19 +278,6 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
     l_run[1] += psum[1];
 }
 
-template <typename OutT>
-__device__ __forceinline__ void store4(OutT* dst, float a, float b, float c, float d);
-
-template <>
-__device__ __forceinline__ void store4<float>(float* dst, float a, float b, float c, float d) {
-    *reinterpret_cast<float4*>(dst) = make_float4(a, b, c, d);
-}
-template <>
-__device__ __forceinline__ void store4<__bf16>(__bf16* dst, float a, float b, float c, float d) {
-    bf16x4 o = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};   // round to nearest even
-    *reinterpret_cast<bf16x4*>(dst) = o;
-}
-
 // kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split).
 template <typename OutT, bool kSplit>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -587,9 +574,9 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq)
-                        store4<OutT>(op + 32 * db + 8 * vq + 4 * g_e,
-                                     oacc[db][qb][4 * vq] * inv[qb], oacc[db][qb][4 * vq + 1] * inv[qb],
-                                     oacc[db][qb][4 * vq + 2] * inv[qb], oacc[db][qb][4 * vq + 3] * inv[qb]);
+                        *reinterpret_cast<float4*>(op + 32 * db + 8 * vq + 4 * g_e) =
+                            make_float4(oacc[db][qb][4 * vq] * inv[qb], oacc[db][qb][4 * vq + 1] * inv[qb],
+                                        oacc[db][qb][4 * vq + 2] * inv[qb], oacc[db][qb][4 * vq + 3] * inv[qb]);
             }
         }
     }

@@ -80,9 +80,8 @@ __device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, cons
 
     // ---- copies: a copy fills 8 rows of 128 bytes; lane L lands at row L/8, chunk L%8 and fetches
     // the source chunk that the swizzle puts there.  Wave `wave` fills x rows 32*wave .. +31
-    // (4 copies) and w rows (BN/8)*wave .. (BN/64 copies); both starts are multiples of 8, so
+    // (4 copies) and w rows (BN/8)*wave .. (BN/64 copies: 4 + BN/64 per wave and stage); both starts are multiples of 8, so
     // the swizzle of row 8u + L/8 of a wave's share is L/8.
-    constexpr int kCopies = 4 + BN / 64;   // per wave per stage
     const int r8 = lane >> 3;
     const int chunk = (lane & 7) ^ lin_swizzle(r8);
     const uint32_t x_off = (uint32_t)(r8 * ldx * 2 + 16 * chunk);      // byte offset of this lane inside an 8-row group
