@@ -353,6 +353,62 @@ def test_bf16_full_size_configs_on_sampled_rows(B, oracle, name, n_samples):
     assert mx <= BF16_MAX and mean <= BF16_MEAN and le <= BF16_LSE
 
 
+def _branch_membership(N, H, branches):
+    """kept[x][h, n]: branch x keeps row n of head h (offset h mod r); seg[x][n]: its segment of that branch."""
+    n = np.arange(N)
+    kept = [np.stack([(n % w) % r == h % r for h in range(H)]) for (w, r) in branches]
+    seg = [n // w for (w, r) in branches]
+    return kept, seg
+
+
+def test_bf16_full_size_zero_queries_closed_form_on_every_row(B):
+    """Every row of the full-size launch, not a sample: with q = 0 all numerators of a row are equal, so lse is
+    the logarithm of the row's key count (each key once per branch that pairs it with the row) and out the
+    mean of those V rows - both computed here in numpy from segment sums, without the oracle."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["throughput"]
+    Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
+    (q, k, v), ex = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
+    out, lse = B.forward(torch.zeros_like(q), k, v, branches, 0.125)
+    vv = ex[2]                                                   # [B, N, H, D] fp64
+    kept, seg = _branch_membership(N, H, branches)
+    num = np.zeros((Bsz, N, H, D))
+    cnt = np.zeros((H, N))
+    for x, (w, r) in enumerate(branches):
+        for h in range(H):
+            m = kept[x][h]
+            sums = np.add.reduceat(np.where(m[None, :, None], vv[:, :, h, :], 0.0), np.arange(0, N, w), axis=1)
+            num[:, m, h, :] += sums[:, seg[x][m], :]
+            cnt[h, m] += w // r
+    ref = num / cnt.T[None, :, :, None]
+    got, got_l = to_f64(out), to_f64(lse)
+    # Rows of one branch: every numerator is exactly 1.  Rows of several branches: numerators m / m_max for keys
+    # held by m branches (1/3, 2/3, 1), and equal numerators all round the same way - the correlated case of
+    # the bound behind BF16_LSE (1.5e-3 here).
+    l_err = np.abs(got_l - np.log(cnt)[None])
+    one_branch = np.broadcast_to((cnt == branches[0][0] // branches[0][1])[None], l_err.shape)
+    assert l_err[one_branch].max() <= 1e-5 and l_err.max() <= BF16_LSE
+    d = np.abs(got - ref)
+    print(f"[zero q, every row] out max-abs {d.max():.3e} mean-abs {d.mean():.3e}", flush=True)
+    assert d.max() <= BF16_MAX and d.mean() <= BF16_MEAN
+
+
+def test_bf16_full_size_constant_v_comes_back_exactly(B):
+    """out is the weighted mean of V rows under the weights the kernel actually uses (the denominator is the sum
+    of the same rounded numerators that enter the second product), so a V whose rows are all one vector of
+    bf16 values must come back as exactly that vector on every row, whatever q and k are."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["throughput"]
+    Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
+    (q, k, v), _ = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
+    row = v[0, 0].clone()                                        # [H, D]: one vector per head
+    vc = row[None, None].expand(Bsz, N, H, D).contiguous()
+    out, _ = B.forward(q, k, vc, branches, 0.125)
+    assert bool((out == vc).all())
+
+
 # ---------------------------------------------------------------- stage entry points
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
