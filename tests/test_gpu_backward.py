@@ -138,6 +138,43 @@ def test_backward_bf16_full_size_on_sampled_images(B, oracle):
             assert mx <= 3e-2 and mean <= 2e-3
 
 
+def test_backward_bf16_full_size_locality_on_every_row(B):
+    """Changing dout of one token changes dq of that token only, and dk / dv of exactly the tokens it holds as
+    keys (same segment of a branch that keeps both, Eq. 1); every other row of the three full-size gradients
+    stays as it was, bit for bit."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["throughput"]
+    Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
+    (q, k, v), _ = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
+    g, _ = _dout(c["seed"], (Bsz, N, H, D), "bf16")
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    first = [x.clone() for x in B.backward(q, k, v, out, lse, g, branches, 0.125)]
+    b_t, t = 5, 2049
+    g2 = g.clone()
+    g2[b_t, t] = -g[b_t, t] + 0.5
+    second = B.backward(q, k, v, out, lse, g2, branches, 0.125)
+    torch.cuda.synchronize()
+    n = np.arange(N)
+    keys_of_t = np.zeros((H, N), dtype=bool)
+    for (w, r) in branches:
+        for h in range(H):
+            kept = (n % w) % r == h % r
+            if kept[t]:
+                keys_of_t[h] |= kept & (n // w == t // w)
+    changed = [(a != b).any(dim=-1).permute(0, 2, 1).cpu().numpy() for a, b in zip(first, second)]   # [B, H, N] each
+    only_t = np.zeros((Bsz, H, N), dtype=bool)
+    only_t[b_t, :, t] = True
+    keys = np.zeros((Bsz, H, N), dtype=bool)
+    keys[b_t] = keys_of_t
+    assert np.array_equal(changed[0], only_t)
+    for name, ch in zip(("dk", "dv"), changed[1:]):
+        assert not (ch & ~keys).any(), name
+        assert ch[keys].mean() >= 0.99, name
+    print(f"[backward locality] keys of the token: {int(keys.sum())}; dk rows changed {int(changed[1].sum())}, "
+          f"dv rows changed {int(changed[2].sum())}", flush=True)
+
+
 @pytest.mark.parametrize("count", [1, 31, 33, 64, 65, 129])
 def test_backward_bf16_list_lengths_around_the_block_sizes(B, oracle, count):
     """Lists of `count` rows: one row (P = 1, dq = dk = 0, dv = dout), and lengths just below, at and

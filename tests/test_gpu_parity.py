@@ -409,6 +409,36 @@ def test_bf16_full_size_constant_v_comes_back_exactly(B):
     assert bool((out == vc).all())
 
 
+def test_bf16_full_size_locality_on_every_row(B):
+    """Changing the K and V rows of one token changes exactly the rows that hold that token as a key (same
+    segment of a branch that keeps both, Eq. 1) and leaves every other row of the full-size launch as it was,
+    bit for bit: a gather that reached outside a row's key lists, or missed a part of them, shows here."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["throughput"]
+    Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
+    (q, k, v), _ = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
+    out0, lse0 = B.forward(q, k, v, branches, 0.125)
+    b_t, t = 3, 1234
+    k2, v2 = k.clone(), v.clone()
+    k2[b_t, t] = -k[b_t, t]
+    v2[b_t, t] = v[b_t, t] + 1.0
+    out1, lse1 = B.forward(q, k2, v2, branches, 0.125)
+    torch.cuda.synchronize()
+    kept, seg = _branch_membership(N, H, branches)
+    touched = np.zeros((H, N), dtype=bool)
+    for x in range(len(branches)):
+        for h in range(H):
+            if kept[x][h][t]:
+                touched[h] |= kept[x][h] & (seg[x] == seg[x][t])
+    changed = ((out0 != out1).any(dim=-1).permute(0, 2, 1) | (lse0 != lse1)).cpu().numpy()      # [B, H, N]
+    expect = np.zeros((Bsz, H, N), dtype=bool)
+    expect[b_t] = touched
+    assert not (changed & ~expect).any()
+    assert changed[expect].mean() >= 0.99
+    print(f"[locality] rows holding the token: {int(expect.sum())}, changed: {int(changed.sum())}", flush=True)
+
+
 # ---------------------------------------------------------------- stage entry points
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
