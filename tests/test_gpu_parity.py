@@ -394,13 +394,14 @@ def test_bf16_full_size_zero_queries_closed_form_on_every_row(B):
     assert d.max() <= BF16_MAX and d.mean() <= BF16_MEAN
 
 
-def test_bf16_full_size_constant_v_comes_back_exactly(B):
+@pytest.mark.parametrize("name", ["throughput", "highres"])
+def test_bf16_full_size_constant_v_comes_back_exactly(B, name):
     """out is the weighted mean of V rows under the weights the kernel actually uses (the denominator is the sum
     of the same rounded numerators that enter the second product), so a V whose rows are all one vector of
     bf16 values must come back as exactly that vector on every row, whatever q and k are."""
     import torch
     from paper_2403_09195_amd import synth
-    c = synth.CONFIGS["throughput"]
+    c = synth.CONFIGS[name]
     Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
     (q, k, v), _ = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
     row = v[0, 0].clone()                                        # [H, D]: one vector per head
@@ -409,17 +410,17 @@ def test_bf16_full_size_constant_v_comes_back_exactly(B):
     assert bool((out == vc).all())
 
 
-def test_bf16_full_size_locality_on_every_row(B):
+@pytest.mark.parametrize("name,b_t,t", [("throughput", 3, 1234), ("highres", 1, 9000)])
+def test_bf16_full_size_locality_on_every_row(B, name, b_t, t):
     """Changing the K and V rows of one token changes exactly the rows that hold that token as a key (same
     segment of a branch that keeps both, Eq. 1) and leaves every other row of the full-size launch as it was,
     bit for bit: a gather that reached outside a row's key lists, or missed a part of them, shows here."""
     import torch
     from paper_2403_09195_amd import synth
-    c = synth.CONFIGS["throughput"]
+    c = synth.CONFIGS[name]
     Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
     (q, k, v), _ = make_qkv(c["seed"], Bsz, N, H, D, "bf16")
     out0, lse0 = B.forward(q, k, v, branches, 0.125)
-    b_t, t = 3, 1234
     k2, v2 = k.clone(), v.clone()
     k2[b_t, t] = -k[b_t, t]
     v2[b_t, t] = v[b_t, t] + 1.0
@@ -436,7 +437,7 @@ def test_bf16_full_size_locality_on_every_row(B):
     expect[b_t] = touched
     assert not (changed & ~expect).any()
     assert changed[expect].mean() >= 0.99
-    print(f"[locality] rows holding the token: {int(expect.sum())}, changed: {int(changed.sum())}", flush=True)
+    print(f"[locality {name}] rows holding the token: {int(expect.sum())}, changed: {int(changed.sum())}", flush=True)
 
 
 # ---------------------------------------------------------------- stage entry points
