@@ -148,3 +148,27 @@ def test_three_layer_stack_end_to_end(B, oracle):
     ws = (torch.empty_like(qkv), torch.empty_like(attn), torch.empty_like(y))
     y2, _, _ = B.encoder_stack(x, wq, wo, H, branches, 0.125, workspace=ws)
     assert y2 is ws[2] and bool((y2 == y).all())
+
+
+def test_full_size_layer_with_identity_projections_is_the_operator(B):
+    """The stack workload's shapes (8 images, 4096 tokens, 12 heads): with W_qkv = [I; I; I] and W_o = I the
+    projections copy their input exactly (one product by 1 per output, the rest by 0), so the layer must equal
+    dfa_forward on x taken as q, k and v, bit for bit - the packed, strided q / k / v views and the [B, N, H*D]
+    hand-over between the three launches, at the size the benchmark runs."""
+    import torch
+    from paper_2403_09195_amd import synth
+    c = synth.CONFIGS["stack_layer"]
+    Bsz, N, H, D, branches = c["B"], c["N"], c["H"], c["D"], c["branches"]
+    E = H * D
+    x = to_device(synth.tensor(c["seed"], 3, (Bsz, N, E), "bf16")[0])
+    eye = torch.eye(E, dtype=torch.bfloat16, device=x.device)
+    wq = torch.cat([eye, eye, eye], dim=0)[None].contiguous()
+    wo = eye[None].contiguous()
+    y, qkv, attn = B.encoder_stack(x, wq, wo, H, branches, 0.125)
+    xh = x.view(Bsz, N, H, D)
+    out, _ = B.forward(xh, xh, xh, branches, 0.125)
+    torch.cuda.synchronize()
+    for t in range(3):
+        assert bool((qkv[:, :, t] == xh).all())
+    assert bool((attn == out).all())
+    assert bool((y.view(Bsz, N, H, D) == out).all())
