@@ -372,25 +372,21 @@ def main():
     peak_const, mhz_const = binding.mfma_peak(False)
     peak_rand, mhz_rand = binding.mfma_peak(True)
 
-    # sampled parity against the oracle (cheap sanity check of what was just timed)
-    from oracle import dfa_oracle
-    rng = np.random.default_rng(1)
-    ns = 96
-    bhn = np.stack([rng.integers(0, Bsz, ns), rng.integers(0, H, ns), rng.integers(0, N, ns)], axis=1).astype(np.int32)
-    o_ref, l_ref = dfa_oracle.forward_rows(*exact, branches, scale, bhn)
-    got = out.float().cpu().numpy().astype(np.float64)[bhn[:, 0], bhn[:, 2], bhn[:, 1]]
-    max_err = float(np.abs(got - o_ref).max())
-
+    # CPU baseline leg: the oracle as it stands, timed on the host cores on the whole workload; its result also
+    # says how far what was just timed is from it (every element of the output)
     cpu = None
+    max_err = None
     if not args.no_cpu_baseline:
+        from oracle import dfa_oracle
         bs = Bsz                                      # the oracle needs only seconds for the whole batch
         sub = tuple(np.ascontiguousarray(a[:bs]) for a in exact)
         t0 = time.perf_counter()
-        dfa_oracle.forward(*sub, branches, scale)
+        o_ref, _ = dfa_oracle.forward(*sub, branches, scale)
         dt = time.perf_counter() - t0
         cpu = {"value": synth.useful_flops(bs, H, N, D, branches) / dt / 1e12, "unit": "TFLOP/s",
                "cores": dfa_oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
                "sample": f"the whole workload: {bs} of {Bsz} images, all {H} heads ({bs * H} independent (b,h) units), fp64"}
+        max_err = float(np.abs(out[:bs].float().cpu().numpy().astype(np.float64) - o_ref).max())
 
     # the second half of the headline metric: one 1024^2 image through all 12 layers of the encoder
     # attention stack (projections included), from a short run of the stack workload
@@ -419,7 +415,7 @@ def main():
         "us_per_image_12_layers_attention_only": 12 * ms_per_step * 1e3 / Bsz,
         "encoder_attention_stack": stack,
         "useful_flops_per_step": flops,
-        "sampled_max_abs_err_vs_oracle": max_err,
+        "max_abs_err_vs_oracle": max_err,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.workload),
