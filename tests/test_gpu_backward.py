@@ -113,10 +113,9 @@ def test_backward_bf16_sam_scale_config(B, oracle):
         assert mx <= 3e-2 and mean <= 2e-3
 
 
-def test_backward_bf16_full_size_on_sampled_images(B, oracle):
-    """The launch the backward benchmark times (16 images, 12 heads, 4096 tokens): every gradient is
-    finite, and three sampled (image, head) pairs are checked in full against the oracle, each as a
-    one-head problem whose explicit offsets are that head's."""
+def test_backward_bf16_full_size_element_by_element(B, oracle):
+    """The launch the backward benchmark times (16 images, 12 heads, 4096 tokens) against the oracle on the same
+    inputs, every element of the three gradients (the oracle needs some ten seconds on the machine's host cores)."""
     import torch
     from paper_2403_09195_amd import synth
     c = synth.CONFIGS["throughput"]
@@ -125,17 +124,12 @@ def test_backward_bf16_full_size_on_sampled_images(B, oracle):
     out, lse = B.forward(q, k, v, c["branches"], 0.125)
     dq, dk, dv = B.backward(q, k, v, out, lse, g, c["branches"], 0.125)
     torch.cuda.synchronize()
-    for t in (dq, dk, dv):
-        assert bool(torch.isfinite(t.float()).all())
-    rng = np.random.default_rng(c["seed"] + 1)
-    for _ in range(3):
-        b, h = int(rng.integers(0, c["B"])), int(rng.integers(0, c["H"]))
-        one = [np.ascontiguousarray(x[b:b + 1, :, h:h + 1]) for x in (*ex, ge)]
-        offs = [[h % r] for _, r in c["branches"]]
-        refs = oracle.backward(*one, c["branches"], 0.125, head_offsets=offs)
-        for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
-            mx, mean = _report(f"throughput b={b} h={h} {name}", to_f64(got[b:b + 1, :, h:h + 1]), ref)
-            assert mx <= 3e-2 and mean <= 2e-3
+    refs = oracle.backward(*ex, ge, c["branches"], 0.125)
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        mx, mean = _report(f"throughput, every element, {name}", to_f64(got), ref)
+        # the per-element bar of test_backward_bf16 is sized for the largest of some 10^5 rounding errors; this is
+        # the largest of 5 * 10^7 per gradient (it reaches 2.9e-2 rms(g) in dq), hence 5e-2; the mean bar is the same
+        assert mx <= 5e-2 and mean <= 2e-3
 
 
 def test_backward_bf16_full_size_locality_on_every_row(B):

@@ -329,28 +329,16 @@ def test_bf16_sam_scale_config_full(B, oracle):
     _check_bf16(out, lse, o_ref, l_ref, "sam-scale B=1")
 
 
-@pytest.mark.parametrize("name,n_samples", [("throughput", 768), ("highres", 256)])
-def test_bf16_full_size_configs_on_sampled_rows(B, oracle, name, n_samples):
-    """Full-size launch (the one the benchmark times); oracle on sampled rows, plus the
-    properties that hold at any size: no NaN, finite lse everywhere (every row is kept by the
-    r = 1 branch), and lse of a row in more branches exceeds ln(keys of one branch) less often."""
+@pytest.mark.parametrize("name", ["throughput", "highres"])
+def test_bf16_full_size_configs_element_by_element(B, oracle, name):
+    """The full-size launches (the first is the one the benchmark times) against the oracle on the same inputs,
+    every element of out and lse: the oracle needs a few seconds for them on the machine's host cores."""
     from paper_2403_09195_amd import synth
     c = synth.CONFIGS[name]
     (q, k, v), ex = make_qkv(c["seed"], c["B"], c["N"], c["H"], c["D"], "bf16")
     out, lse = B.forward(q, k, v, c["branches"], 0.125)
-    import torch
-    torch.cuda.synchronize()
-    assert bool(torch.isfinite(out.float()).all()) and bool(torch.isfinite(lse).all())
-    rng = np.random.default_rng(c["seed"])
-    bhn = np.stack([rng.integers(0, c["B"], n_samples), rng.integers(0, c["H"], n_samples),
-                    rng.integers(0, c["N"], n_samples)], axis=1).astype(np.int32)
-    o_ref, l_ref = oracle.forward_rows(*ex, c["branches"], 0.125, bhn)
-    got_o = to_f64(out)[bhn[:, 0], bhn[:, 2], bhn[:, 1]]
-    got_l = to_f64(lse)[bhn[:, 0], bhn[:, 1], bhn[:, 2]]
-    mx, mean = error_stats(got_o, o_ref)
-    le = float(np.abs(got_l - l_ref).max())
-    print(f"[{name}] sampled {n_samples} rows: out max-abs {mx:.3e} mean-abs {mean:.3e} lse {le:.3e}", flush=True)
-    assert mx <= BF16_MAX and mean <= BF16_MEAN and le <= BF16_LSE
+    o_ref, l_ref = oracle.forward(*ex, c["branches"], 0.125)
+    _check_bf16(out, lse, o_ref, l_ref, f"{name}, every element")
 
 
 def _branch_membership(N, H, branches):
