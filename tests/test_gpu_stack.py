@@ -100,13 +100,16 @@ def _rel(got, ref):
     return float(d.max()) / rms, float(d.mean()) / rms
 
 
-def test_one_layer_each_step_against_the_oracle(B, oracle):
-    """One layer, checked step by step: the oracle is fed the GPU's own (bf16) input of each step, so
-    every step is held to its own bar: projections to the rounding bar above, attention to the
+@pytest.mark.parametrize("Bsz,N,H,branches", [
+    (2, 512, 4, [(128, 1), (256, 2), (512, 4)]),
+    (8, 4096, 12, [(1024, 1), (2048, 2), (4096, 4)]),        # a layer of the stack workload at its full size
+])
+def test_one_layer_each_step_against_the_oracle(B, oracle, Bsz, N, H, branches):
+    """One layer, checked step by step, every element: the oracle is fed the GPU's own (bf16) input of each
+    step, so every step is held to its own bar: projections to the rounding bar above, attention to the
     operator's bars scaled by the size of its values."""
-    Bsz, N, H, D = 2, 512, 4, 64
+    D = 64
     E = H * D
-    branches = [(128, 1), (256, 2), (512, 4)]
     x, xe, wq, wqe, wo, woe = _stack_inputs(410, Bsz, N, H, D, 1)
     y, qkv, attn = B.encoder_stack(x, wq, wo, H, branches, 0.125)
     qkv_g, attn_g, y_g = to_f64(qkv), to_f64(attn), to_f64(y)
