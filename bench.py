@@ -401,7 +401,9 @@ def main():
             stack = {"error": repr(exc)}
 
     line = {
-        "metric": "dilated-attention TFLOP/s (useful attention FLOPs, 4*D per kept query-key pair)",
+        # the metric as the task definition words it; `value` is its first part (useful attention FLOPs, 4*D per
+        # kept (query, key) pair), the other two parts are pct_of_mfma_peak and encoder_attention_stack below
+        "metric": "dilated-attention TFLOP/s + % MFMA peak; \u00b5s per 1024\u00b2 image (all layers)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
