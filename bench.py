@@ -224,8 +224,11 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 2000 for the default line, about 0.6 s of launches back to back, so that the "
+                         "fixed cost of starting and draining the queue, about 1.4 ms, does not weigh on the per-step figure; "
+                         "200 for the other reports)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: 50 and 20)")
     ap.add_argument("--workload", default=WORKLOAD, help="name in synth.CONFIGS (default: throughput)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true",
@@ -253,6 +256,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
+    other_report = args.stages or args.stack or args.sweep or args.tile_cost or args.backward or args.copy_calibration
+    if args.steps is None:
+        args.steps = 200 if other_report or args.workload != WORKLOAD else 2000
+    if args.warmup is None:
+        args.warmup = 20 if other_report or args.workload != WORKLOAD else 50
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs: "
                  "(b, h) units are independent, so N GPUs would each run this same kernel on B/N images). "
