@@ -162,7 +162,7 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
           torch.empty((Bsz, N, E), dtype=torch.bfloat16, device="cuda"))
 
     def run():
-        return binding.encoder_stack(x, wq, wo, H, branches, scale, workspace=ws)
+        return binding.encoder_stack(x, wq, wo, H, branches, scale, buffers=ws)
 
     for _ in range(warmup):
         run()

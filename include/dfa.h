@@ -32,15 +32,21 @@
  *   - D must be 64.  Non-causal, no mask, no bias.
  *   - Return value: DFA_OK (0) or a negative dfa_status_t.  Argument errors are found on
  *     the host before anything is enqueued.  No C++ exception crosses this boundary.
- *   - dfa_forward / dfa_forward_branch keep a small per-process cache of launch plans
- *     (tile lists in device memory, a few hundred KB each), keyed by device and problem
- *     shape.  The first call with a new shape allocates and uploads its plan
+ *   - The attention entry points keep a per-process cache of launch plans (tile lists in
+ *     device memory, read-only once built, a few hundred KB each), keyed by device and
+ *     problem shape.  The first call with a new shape allocates and uploads its plan
  *     (synchronously); later calls with that shape allocate nothing and only enqueue
- *     kernels, so they can be recorded into a HIP graph (call once before capturing).
- *     dfa_release_plans() frees them.  A bf16 dfa_forward whose plan has fewer workgroups than the
- *     chip has compute units (a single image, say) walks every tile with several workgroups and
- *     merges their fp32 partial results; those live in the plan too (up to 4 x B*N*H*65 floats),
- *     so two such calls with the same shape must not overlap on different streams.
+ *     kernels, so they can be recorded into a HIP graph (call once before capturing).  The
+ *     cache holds the 64 most recently used plans (at most 256 MiB); a plan that falls out is
+ *     freed (which synchronises its device) once no call is using it.  dfa_release_plans()
+ *     empties the cache.  Calls may come from several threads and on several streams at once:
+ *     a plan is shared and never written after its upload.
+ *   - Workspace.  A bf16 dfa_forward with fewer workgroups than the chip has room for (a single
+ *     image, say) is faster when every tile is walked by several workgroups whose fp32 partial
+ *     results are merged afterwards.  Those partial results live in a workspace that the caller
+ *     owns: dfa_workspace_bytes() says how much the shape needs (0 = none), and each call that
+ *     may overlap another one needs a workspace of its own.  With workspace == NULL the call
+ *     runs unsplit: same results to within rounding, slower for such shapes.
  */
 #ifndef DFA_H
 #define DFA_H
@@ -66,7 +72,8 @@ typedef enum {
     DFA_ERR_DTYPE = -4,     /* unknown dfa_dtype_t                                           */
     DFA_ERR_ALIGN = -5,     /* a base pointer or stride breaks the 16-byte row alignment     */
     DFA_ERR_LAUNCH = -6,    /* the HIP runtime refused an allocation, copy or launch         */
-    DFA_ERR_TOO_LARGE = -7  /* index arithmetic would overflow the kernel's 32-bit counters  */
+    DFA_ERR_TOO_LARGE = -7, /* index arithmetic would overflow the kernel's 32-bit counters  */
+    DFA_ERR_WORKSPACE = -8  /* a workspace was passed that is smaller than dfa_workspace_bytes() */
 } dfa_status_t;
 
 typedef enum { DFA_BF16 = 0, DFA_F32 = 1 } dfa_dtype_t;
@@ -97,6 +104,17 @@ int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t *h
                          int32_t *d_out_idx, void *stream);
 
 /*
+ * Bytes of device workspace that dfa_forward / dfa_encoder_stack use for this shape on the current
+ * device (section 3.1's operator has no such notion: this is the room for the fp32 partial results
+ * of a launch whose tiles are each walked by several workgroups, see "Workspace" above).  0 when the
+ * shape needs none, for dt = DFA_F32, and for arguments dfa_forward would reject.  Host only: builds
+ * the launch plan on the host, allocates nothing on the device; asks the current device for its
+ * compute-unit count (the MI355X's when there is no device).
+ */
+size_t dfa_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                           const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets);
+
+/*
  * Main entry: gather (Eq. 1) + per-segment attention (Eq. 2) + placement (Eq. 3) +
  * log-sum-exp merge of the nb branches, in one fused kernel.
  *   q, k, v       device, dtype dt, strided as described above
@@ -105,6 +123,9 @@ int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t *h
  *   lse           device, fp32 contiguous [B, H, N], natural log of the sum of
  *                 exp(scale * q.k) over the row's keys (each key counted once per branch
  *                 that pairs it with the row); -inf for rows kept by no branch.  May be NULL.
+ *   workspace     device, 16-byte aligned, at least dfa_workspace_bytes() of this shape, written and
+ *                 read by this call only (contents need not be kept between calls); or NULL.  Too
+ *                 small a non-NULL workspace is DFA_ERR_WORKSPACE.
  * dt = DFA_BF16: bf16 operands on the matrix cores, fp32 accumulation and softmax
  * statistics, probabilities rounded to bf16 before the product with V, result rounded to
  * bf16.  The softmax denominator is the fp32 sum of those rounded probabilities, so out is
@@ -116,7 +137,7 @@ int dfa_forward(const void *q, const void *k, const void *v,
                 dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
                 int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
                 const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
-                void *out, float *lse, void *stream);
+                void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Backward of dfa_forward: gradients with respect to q, k, v for a gradient dout of the merged
@@ -219,42 +240,21 @@ int dfa_linear(const void *x, const void *w, void *y, int64_t M, int32_t N, int3
  *   attn_ws  device bf16 [B][N][H][D]      workspace, holds the last layer's attention output
  *   y        device bf16 [B][N][E]         x_layers; also used for every intermediate x_l
  *                                          (y may be the same buffer as x: x is then overwritten)
- *   branches, head_offsets, scale          as in dfa_forward
+ *   branches, head_offsets, scale, workspace, workspace_bytes    as in dfa_forward (one workspace
+ *                                          serves every layer)
  * (B * N) % 256 == 0 and E % 128 == 0 are required (DFA_ERR_SHAPE otherwise); D must be 64.
- * Three launches per layer on `stream`, nothing else; allocates only what dfa_forward's plan
- * cache allocates on first use.
+ * Every argument is checked before the first launch.  Three launches per layer on `stream` (four
+ * where the attention launch is split); allocates only what the plan cache allocates on first use.
  */
 int dfa_encoder_stack(const void *x, const void *w_qkv, const void *w_o, int32_t layers,
                       int32_t B, int32_t H, int32_t N, int32_t D, float scale,
                       const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
-                      void *qkv_ws, void *attn_ws, void *y, void *stream);
+                      void *qkv_ws, void *attn_ws, void *y, void *workspace, size_t workspace_bytes,
+                      void *stream);
 
-/* Frees every cached launch plan of every device.  Synchronises the devices involved. */
+/* Empties the plan cache of every device; a plan is freed (its device synchronised) as soon as no
+ * call is using it any more. */
 int dfa_release_plans(void);
-
-/*
- * Times `iters` back-to-back dfa_forward launches with HIP events recorded on `stream`
- * (the stream the kernel runs on) and returns the mean milliseconds per launch in *ms.
- * Arguments as dfa_forward.  Synchronises `stream`.  For benchmarks.
- */
-int dfa_forward_timed(const void *q, const void *k, const void *v,
-                      dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
-                      int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
-                      const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
-                      void *out, float *lse, void *stream, int32_t iters, float *ms);
-
-/*
- * Measurement aid (no part of the operator): what the matrix cores sustain on their own, the
- * ceiling that the kernels' MFMA rooflines are also quoted against.  Runs a loop of
- * independent v_mfma_f32_32x32x16_bf16 on the whole chip (two waves per SIMD, no memory
- * traffic) on the default stream and synchronises.
- *   random_operands  0: small constant operands; 1: pseudo-random bf16 operands (more bits
- *                    toggle, the sustained clock is lower)
- *   tflops           out, host: achieved TFLOP/s
- *   shader_mhz       out, host: shader clock during the loop (cycle counter / 100 MHz wall counter)
- * Allocates and frees a few bytes of device memory.
- */
-int dfa_mfma_peak(int32_t random_operands, float *tflops, float *shader_mhz);
 
 #ifdef __cplusplus
 }

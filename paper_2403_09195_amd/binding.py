@@ -14,12 +14,15 @@ from .build import LIB_PATH
 
 DFA_BF16, DFA_F32 = 0, 1
 DFA_MAX_BRANCHES = 8
+DFA_ERR_WORKSPACE = -8
 
+# include/dfa.h (the operator) and include/dfa_bench.h (measurement aids)
 EXPORTS = [
-    "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_forward",
+    "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_workspace_bytes", "dfa_forward",
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
-    "dfa_release_plans", "dfa_forward_timed", "dfa_linear", "dfa_encoder_stack", "dfa_mfma_peak", "dfa_backward",
+    "dfa_release_plans", "dfa_linear", "dfa_encoder_stack", "dfa_backward",
 ]
+BENCH_EXPORTS = ["dfa_forward_timed", "dfa_mfma_peak"]
 
 
 class Branch(ctypes.Structure):
@@ -67,7 +70,8 @@ def lib():
         L.dfa_index_map.argtypes = [i32, i32, Branch, _i32p, _i32p]
         L.dfa_index_map_device.argtypes = [i32, i32, Branch, _i32p, vp, vp]
         fwd = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, ctypes.c_int, f32,
-               ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp]
+               ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp, ctypes.c_size_t, vp]
+        L.dfa_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(Branch), i32, _i32p]
         L.dfa_forward.argtypes = fwd
         L.dfa_forward_timed.argtypes = fwd + [i32, ctypes.POINTER(f32)]
         L.dfa_forward_branch.argtypes = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32,
@@ -80,13 +84,14 @@ def lib():
         i64 = ctypes.c_int64
         L.dfa_linear.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
         L.dfa_encoder_stack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, ctypes.POINTER(Branch), i32,
-                                        _i32p, vp, vp, vp, vp]
+                                        _i32p, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.dfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, ctypes.c_int,
                                    f32, ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp, vp, vp]
         L.dfa_mfma_peak.argtypes = [i32, ctypes.POINTER(f32), ctypes.POINTER(f32)]
-        for name in EXPORTS:
-            if name != "dfa_error_string":
+        for name in EXPORTS + BENCH_EXPORTS:
+            if name not in ("dfa_error_string", "dfa_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int
+        L.dfa_workspace_bytes.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -165,30 +170,62 @@ def index_map_device(N, H, w, r, head_offsets=None):
     return out
 
 
-def _fwd_args(q, k, v, branches, scale, head_offsets, out, lse):
+_ws_bytes = {}
+
+
+def workspace_bytes(B, H, N, D, dtype_code, branches, head_offsets=None):
+    """Bytes of workspace dfa_forward uses for this shape on the current device (0 = none)."""
+    offs = _i32_array(head_offsets)
+    key = (B, H, N, D, dtype_code, tuple(tuple(b) for b in branches), tuple(offs) if offs is not None else None)
+    if key not in _ws_bytes:
+        br, nb = _branches(branches)
+        _ws_bytes[key] = int(lib().dfa_workspace_bytes(B, H, N, D, dtype_code, br, nb, offs))
+    return _ws_bytes[key]
+
+
+def _workspace(workspace, q, branches, head_offsets):
+    """(pointer, bytes, keep-alive) of the workspace argument: a uint8 tensor, None (NULL: unsplit launch)
+    or "auto" (a fresh tensor of the size the library asks for)."""
+    import torch
+    if isinstance(workspace, str) and workspace == "auto":
+        B, N, H, D = q.shape
+        need = workspace_bytes(B, H, N, D, _dtype_code(q), branches, head_offsets)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device) if need else None
+    if workspace is None:
+        return ctypes.c_void_p(None), ctypes.c_size_t(0), None
+    _gpu(workspace, "workspace")
+    return ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()), workspace
+
+
+def _fwd_args(q, k, v, branches, scale, head_offsets, out, lse, workspace):
     for t, nm in ((q, "q"), (k, "k"), (v, "v"), (out, "out")):
         _gpu(t, nm)
     B, N, H, D = q.shape
     br, nb = _branches(branches)
+    ws_ptr, ws_bytes, keep = _workspace(workspace, q, branches, head_offsets)
     return [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
             _strides(q), _strides(k), _strides(v), B, H, N, D, _dtype_code(q), ctypes.c_float(scale),
             br, nb, _i32_array(head_offsets), ctypes.c_void_p(out.data_ptr()),
-            ctypes.c_void_p(lse.data_ptr() if lse is not None else None), _stream()]
+            ctypes.c_void_p(lse.data_ptr() if lse is not None else None), ws_ptr, ws_bytes, _stream()], keep
 
 
-def forward(q, k, v, branches, scale, head_offsets=None, out=None, lse=None, want_lse=True):
-    """Fused dilated attention.  q, k, v [B, N, H, D] (may be strided views) -> (out, lse)."""
+def forward(q, k, v, branches, scale, head_offsets=None, out=None, lse=None, want_lse=True, workspace="auto"):
+    """Fused dilated attention.  q, k, v [B, N, H, D] (may be strided views) -> (out, lse).
+    workspace: uint8 GPU tensor of workspace_bytes(...), None for no workspace, "auto" to allocate one."""
     import torch
     B, N, H, D = q.shape
     if out is None:
         out = torch.empty((B, N, H, D), dtype=q.dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
-    _check(lib().dfa_forward(*_fwd_args(q, k, v, branches, scale, head_offsets, out, lse)), "dfa_forward")
+    args, keep = _fwd_args(q, k, v, branches, scale, head_offsets, out, lse, workspace)
+    _check(lib().dfa_forward(*args), "dfa_forward")
+    if keep is not None and hasattr(keep, "record_stream"):
+        keep.record_stream(torch.cuda.current_stream())     # the launch reads it after this function returns
     return out, lse
 
 
-def forward_timed(q, k, v, branches, scale, iters, head_offsets=None, out=None, lse=None):
+def forward_timed(q, k, v, branches, scale, iters, head_offsets=None, out=None, lse=None, workspace="auto"):
     """Mean milliseconds per dfa_forward launch over `iters` launches (HIP events on the stream)."""
     import torch
     B, N, H, D = q.shape
@@ -197,8 +234,9 @@ def forward_timed(q, k, v, branches, scale, iters, head_offsets=None, out=None, 
     if lse is None:
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     ms = ctypes.c_float(0.0)
-    args = _fwd_args(q, k, v, branches, scale, head_offsets, out, lse) + [int(iters), ctypes.byref(ms)]
-    _check(lib().dfa_forward_timed(*args), "dfa_forward_timed")
+    args, keep = _fwd_args(q, k, v, branches, scale, head_offsets, out, lse, workspace)
+    _check(lib().dfa_forward_timed(*(args + [int(iters), ctypes.byref(ms)])), "dfa_forward_timed")
+    del keep            # the call synchronises the stream
     return ms.value
 
 
@@ -278,11 +316,11 @@ def linear(x, w, out=None):
     return y
 
 
-def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, workspace=None):
+def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, buffers=None, workspace="auto"):
     """`layers` attention layers back to back: x [B, N, E] bf16, w_qkv [layers, 3E, E], w_o [layers, E, E].
 
     Returns (y [B, N, E], qkv of the last layer [B, N, 3, H, D], attention output of the last layer
-    [B, N, H, D]).  `workspace` = (qkv, attn, y) tensors to reuse."""
+    [B, N, H, D]).  `buffers` = (qkv, attn, y) tensors to reuse; `workspace` as in forward()."""
     import torch
     for t, nm in ((x, "x"), (w_qkv, "w_qkv"), (w_o, "w_o")):
         _gpu(t, nm)
@@ -293,17 +331,21 @@ def encoder_stack(x, w_qkv, w_o, H, branches, scale, head_offsets=None, workspac
     D = E // H
     if tuple(w_qkv.shape) != (layers, 3 * E, E) or tuple(w_o.shape) != (layers, E, E) or H * D != E:
         raise ValueError("encoder_stack: weight shapes do not match x")
-    if workspace is None:
-        workspace = (torch.empty((B, N, 3, H, D), dtype=torch.bfloat16, device=x.device),
-                     torch.empty((B, N, H, D), dtype=torch.bfloat16, device=x.device),
-                     torch.empty((B, N, E), dtype=torch.bfloat16, device=x.device))
-    qkv, attn, y = workspace
+    if buffers is None:
+        buffers = (torch.empty((B, N, 3, H, D), dtype=torch.bfloat16, device=x.device),
+                   torch.empty((B, N, H, D), dtype=torch.bfloat16, device=x.device),
+                   torch.empty((B, N, E), dtype=torch.bfloat16, device=x.device))
+    qkv, attn, y = buffers
     br, nb = _branches(branches)
     vp = ctypes.c_void_p
+    ws_ptr, ws_bytes, keep = _workspace(workspace, qkv[:, :, 0], branches, head_offsets)
     _check(lib().dfa_encoder_stack(vp(x.data_ptr()), vp(w_qkv.data_ptr()), vp(w_o.data_ptr()), layers, B, H, N, D,
                                    ctypes.c_float(scale), br, nb, _i32_array(head_offsets),
-                                   vp(qkv.data_ptr()), vp(attn.data_ptr()), vp(y.data_ptr()), _stream()),
+                                   vp(qkv.data_ptr()), vp(attn.data_ptr()), vp(y.data_ptr()), ws_ptr, ws_bytes,
+                                   _stream()),
            "dfa_encoder_stack")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream())
     return y, qkv, attn
 
 

@@ -4,12 +4,15 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <list>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <vector>
 
 #include "../../include/dfa.h"
+#include "../../include/dfa_bench.h"
 #include "dfa_device.h"
 #include "dfa_plan.h"
 
@@ -17,6 +20,8 @@ namespace {
 
 using namespace dfa;
 
+// A launch plan in device memory.  Immutable once built, shared by every call with its shape (also from
+// several threads and streams); freed when the cache has dropped it and the last call using it has returned.
 struct DevicePlan {
     void* base = nullptr;
     const int32_t* rows = nullptr;
@@ -24,89 +29,175 @@ struct DevicePlan {
     const Item* items = nullptr;
     int32_t n_items = 0;
     int device = 0;
-    // launches with few workgroups walk every tile with `split` workgroups (see launch_fwd_bf16_split);
-    // their fp32 partial results go here: out [split][B,N,H,D], then lse [split][B,H,N]
+    size_t bytes = 0;
+    // launches with few workgroups walk every tile with `split` workgroups (see launch_fwd_bf16_split)
+    // when the caller brings a workspace for their fp32 partial results
     int32_t split = 1;
-    float* split_out = nullptr;
-    float* split_lse = nullptr;
+    bool owned = true;          // base came from hipMalloc and is freed with the plan
+
+    DevicePlan() = default;
+    DevicePlan(const DevicePlan&) = delete;
+    DevicePlan& operator=(const DevicePlan&) = delete;
+    ~DevicePlan() {
+        if (!base || !owned) return;
+        int cur = 0;
+        const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+        // kernels still reading the plan finish first
+        if (hipSetDevice(device) == hipSuccess) {
+            (void)hipDeviceSynchronize();
+            (void)hipFree(base);
+        }
+        if (have_cur) (void)hipSetDevice(cur);
+    }
+};
+using PlanRef = std::shared_ptr<const DevicePlan>;
+
+// The host plan laid out as the kernels read it: rows, then key progressions (plus one spare entry: a tile
+// without progressions still reads inside the array), then launch items, each part 256-byte aligned.
+struct PackedPlan {
+    std::vector<char> bytes;
+    size_t off_segs = 0, off_items = 0;
+    int32_t n_items = 0;
+    int32_t split = 1;
 };
 
-constexpr int kChipWorkgroupSlots = 512;    // 256 CUs x 2 workgroups of the bf16 forward kernel
-constexpr int kMaxSplit = 4;
-constexpr int kMinShareSteps = 8;           // 64-key steps a workgroup of a split launch should at least walk
-
-std::mutex g_mu;
-std::map<std::vector<int32_t>, DevicePlan> g_plans;
-
-constexpr int kPlanOrder = 3;   // launch order of build_plan (see dfa_plan.cpp)
+constexpr int kPlanOrder = 3;              // launch order of build_plan (see dfa_plan.cpp)
+constexpr size_t kMaxCachedPlans = 64;     // least recently used plans beyond these bounds are dropped
+constexpr size_t kMaxCachedBytes = (size_t)256 << 20;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Looks the plan up, building and uploading it on first use.  Holds g_mu.
-int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-             const int32_t* offsets, DevicePlan* out) {
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return DFA_ERR_LAUNCH;
+// fp32 partial results of a split launch: out [split][B, N, H, D], then lse [split][B, H, N]
+size_t split_bytes(int32_t split, int64_t rows_total) {
+    return split >= 2 ? align256((size_t)split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float)) : 0;
+}
+
+int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets,
+              const ChipShape& chip, PackedPlan* out) {
+    HostPlan hp;
+    build_plan(B, H, N, br, nb, offsets, kPlanOrder, chip, &hp);
+    if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
+    const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
+    const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
+    const size_t b_items = align256(hp.items.size() * sizeof(Item));
+    out->bytes.assign(b_rows + b_segs + b_items, 0);
+    out->off_segs = b_rows;
+    out->off_items = b_rows + b_segs;
+    if (!hp.rows.empty()) std::memcpy(out->bytes.data(), hp.rows.data(), hp.rows.size() * sizeof(int32_t));
+    if (!hp.segs.empty()) std::memcpy(out->bytes.data() + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg));
+    if (!hp.items.empty()) std::memcpy(out->bytes.data() + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item));
+    out->n_items = (int32_t)hp.items.size();
+    out->split = split_factor(hp, chip);
+    return DFA_OK;
+}
+
+void point_plan(DevicePlan* dp, void* base, const PackedPlan& pp, int device) {
+    char* b = static_cast<char*>(base);
+    dp->base = base;
+    dp->rows = reinterpret_cast<const int32_t*>(b);
+    dp->segs = reinterpret_cast<const KeySeg*>(b + pp.off_segs);
+    dp->items = reinterpret_cast<const Item*>(b + pp.off_items);
+    dp->n_items = pp.n_items;
+    dp->device = device;
+    dp->bytes = pp.bytes.size();
+    dp->split = pp.split;
+}
+
+std::vector<int32_t> plan_key(int device, int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+                              const int32_t* offsets) {
     std::vector<int32_t> key = {device, B, H, N, nb, offsets ? 1 : 0};
     for (int x = 0; x < nb; ++x) {
         key.push_back(br[x].w);
         key.push_back(br[x].r);
     }
     if (offsets) key.insert(key.end(), offsets, offsets + (size_t)nb * H);
+    return key;
+}
 
+std::mutex g_mu;
+// plan cache, most recently used first
+using PlanKey = std::vector<int32_t>;
+std::list<std::pair<PlanKey, PlanRef>> g_lru;
+std::map<PlanKey, std::list<std::pair<PlanKey, PlanRef>>::iterator> g_plans;
+size_t g_cached_bytes = 0;
+std::map<int, ChipShape> g_chips;
+
+// Number of compute units and of accelerator dies of a device, read once per device.  Holds g_mu.
+int chip_of(int device, ChipShape* out) {
     std::lock_guard<std::mutex> lock(g_mu);
-    auto it = g_plans.find(key);
-    if (it != g_plans.end()) {
-        *out = it->second;
-        return DFA_OK;
+    auto it = g_chips.find(device);
+    if (it == g_chips.end()) {
+        ChipShape c;
+        int cus = 0, dies = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+            return DFA_ERR_LAUNCH;
+        if (hipDeviceGetAttribute(&dies, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || dies <= 0) {
+            (void)hipGetLastError();
+            dies = 1;
+        }
+        c.cus = cus;
+        c.dies = dies;
+        it = g_chips.emplace(device, c).first;
     }
-    HostPlan hp;
-    build_plan(B, H, N, br, nb, offsets, kPlanOrder, &hp);
-    if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
-    const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
-    const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
-    const size_t b_items = align256(hp.items.size() * sizeof(Item));
-    DevicePlan dp;
-    dp.device = device;
-    // fewer workgroups than CUs: the launch is as long as its longest tile's walk, so split the walks
-    size_t b_split = 0;
-    const int64_t rows_total = (int64_t)B * N * H;
-    if (hp.items.size() * 2 <= (size_t)kChipWorkgroupSlots) {
-        // a share of fewer than kMinShareSteps steps is not worth a partial result and its merge
-        int64_t longest = 0;
-        for (const Tile& t : hp.tiles) longest = std::max<int64_t>(longest, t.n_steps);
-        dp.split = (int32_t)std::min<int64_t>(std::min<int64_t>(kMaxSplit, longest / kMinShareSteps),
-                                              kChipWorkgroupSlots / (int)std::max<size_t>(hp.items.size(), 1));
-        if (dp.split >= 2) b_split = align256((size_t)dp.split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float));
-        else dp.split = 1;
+    *out = it->second;
+    return DFA_OK;
+}
+
+int current_chip(int* device, ChipShape* chip) {
+    if (hipGetDevice(device) != hipSuccess) return DFA_ERR_LAUNCH;
+    return chip_of(*device, chip);
+}
+
+// Looks the plan of the current device up, building and uploading it on first use (the only device
+// allocation the library makes).  Plans pushed out of the cache are freed once no call holds them.
+int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+             const int32_t* offsets, PlanRef* out) {
+    int device = 0;
+    ChipShape chip;
+    int rc = current_chip(&device, &chip);
+    if (rc != DFA_OK) return rc;
+    PlanKey key = plan_key(device, B, H, N, br, nb, offsets);
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_plans.find(key);
+        if (it != g_plans.end()) {
+            g_lru.splice(g_lru.begin(), g_lru, it->second);
+            *out = it->second->second;
+            return DFA_OK;
+        }
     }
-    if (hipMalloc(&dp.base, b_rows + b_segs + b_items + b_split) != hipSuccess) {
+    // built outside the lock: two threads may both build a new shape, the second result replaces the first
+    PackedPlan pp;
+    rc = pack_plan(B, H, N, br, nb, offsets, chip, &pp);
+    if (rc != DFA_OK) return rc;
+    auto dp = std::make_shared<DevicePlan>();
+    void* base = nullptr;
+    if (hipMalloc(&base, pp.bytes.size()) != hipSuccess) {
         (void)hipGetLastError();   // reported here; a later launch's check must not see it again
         return DFA_ERR_LAUNCH;
     }
-    char* base = static_cast<char*>(dp.base);
-    bool ok = true;
-    ok = ok && hipMemcpy(base, hp.rows.data(), hp.rows.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
-    if (!hp.segs.empty())
-        ok = ok && hipMemcpy(base + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(base + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item), hipMemcpyHostToDevice) == hipSuccess;
-    if (!ok) {
-        (void)hipFree(dp.base);
-        return DFA_ERR_LAUNCH;
-    }
-    dp.rows = reinterpret_cast<const int32_t*>(base);
-    dp.segs = reinterpret_cast<const KeySeg*>(base + b_rows);
-    dp.items = reinterpret_cast<const Item*>(base + b_rows + b_segs);
-    dp.n_items = (int32_t)hp.items.size();
-    if (dp.split >= 2) {
-        dp.split_out = reinterpret_cast<float*>(base + b_rows + b_segs + b_items);
-        dp.split_lse = dp.split_out + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
-    }
-    try {
-        g_plans[key] = dp;
-    } catch (const std::bad_alloc&) {
-        (void)hipFree(dp.base);
-        throw;
+    point_plan(dp.get(), base, pp, device);
+    if (hipMemcpy(base, pp.bytes.data(), pp.bytes.size(), hipMemcpyHostToDevice) != hipSuccess) return DFA_ERR_LAUNCH;
+
+    std::vector<PlanRef> dropped;      // released after the lock: freeing synchronises the device
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_plans.find(key);
+        if (it != g_plans.end()) {
+            g_cached_bytes -= it->second->second->bytes;
+            dropped.push_back(it->second->second);
+            g_lru.erase(it->second);
+            g_plans.erase(it);
+        }
+        g_lru.emplace_front(key, dp);
+        g_plans[key] = g_lru.begin();
+        g_cached_bytes += dp->bytes;
+        while (g_lru.size() > 1 && (g_lru.size() > kMaxCachedPlans || g_cached_bytes > kMaxCachedBytes)) {
+            g_cached_bytes -= g_lru.back().second->bytes;
+            dropped.push_back(g_lru.back().second);
+            g_plans.erase(g_lru.back().first);
+            g_lru.pop_back();
+        }
     }
     *out = dp;
     return DFA_OK;
@@ -153,10 +244,11 @@ int make_offsets(const int32_t* head_offsets, int32_t H, int32_t r, HeadOffsets*
     return DFA_OK;
 }
 
-int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
-                 dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
-                 float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
-                 void* out, bool out_f32, float* lse, void* stream) {
+// Argument checks of the attention entry points (everything that can be found without the GPU).
+int check_forward_args(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                       dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                       float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                       const void* out, const float* lse) {
     if (!q || !k || !v || !out) return DFA_ERR_NULL;
     int rc = check_common(B, H, N, D, dt);
     if (rc != DFA_OK) return rc;
@@ -166,14 +258,17 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     const int es = elem_size(dt);
     if (!aligned_rows(q, sq, es) || !aligned_rows(k, sk, es) || !aligned_rows(v, sv, es)) return DFA_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(out) % 16 || (lse && reinterpret_cast<uintptr_t>(lse) % 4)) return DFA_ERR_ALIGN;
-
     // the copy lanes address a 64-key step with 32-bit byte offsets from its first row
     if (sk.n <= 0 || sv.n <= 0 || sq.n <= 0) return DFA_ERR_TOO_LARGE;
     if (64 * max_key_stride(branches, nb) * std::max(sk.n, sv.n) * es + 128 >= ((int64_t)1 << 31)) return DFA_ERR_TOO_LARGE;
-    DevicePlan dp;
-    rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
-    if (rc != DFA_OK) return rc;
+    return DFA_OK;
+}
 
+// Enqueues the launches of one forward call on a plan.  split_ws: room for the plan's split partial
+// results (split_bytes) or nullptr, in which case a launch with few workgroups runs unsplit.
+int launch_forward(const DevicePlan& dp, const void* q, const void* k, const void* v, dfa_strides_t sq,
+                   dfa_strides_t sk, dfa_strides_t sv, int32_t B, int32_t H, int32_t N, dfa_dtype_t dt,
+                   float scale, void* out, bool out_f32, float* lse, float* split_ws, void* stream) {
     FwdParams p;
     p.q = q; p.k = k; p.v = v;
     p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
@@ -185,12 +280,15 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     p.split = 1; p.part_rows = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (dt == DFA_BF16 && !out_f32 && dp.split >= 2) {
+    if (dt == DFA_BF16 && !out_f32 && dp.split >= 2 && split_ws) {
         // few workgroups: partial results per share of the key walk, then their log-sum-exp merge
-        p.out = dp.split_out; p.lse = dp.split_lse;
-        p.split = dp.split; p.part_rows = (int64_t)B * N * H;
+        const int64_t rows_total = (int64_t)B * N * H;
+        float* part_out = split_ws;
+        float* part_lse = split_ws + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
+        p.out = part_out; p.lse = part_lse;
+        p.split = dp.split; p.part_rows = rows_total;
         e = launch_fwd_bf16_split(p, dp.n_items, st);
-        if (e == hipSuccess) e = launch_merge(dp.split_out, dp.split_lse, dp.split, B, H, N, true, out, lse, st);
+        if (e == hipSuccess) e = launch_merge(part_out, part_lse, dp.split, B, H, N, true, out, lse, st);
     } else if (dt == DFA_BF16) {
         e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
     } else {
@@ -199,11 +297,29 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     return e == hipSuccess ? DFA_OK : DFA_ERR_LAUNCH;
 }
 
+int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                 dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                 float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                 void* out, bool out_f32, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_forward_args(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse);
+    if (rc != DFA_OK) return rc;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return DFA_ERR_ALIGN;
+    PlanRef dp;
+    rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+    if (rc != DFA_OK) return rc;
+    float* split_ws = nullptr;
+    if (workspace && dt == DFA_BF16 && !out_f32 && dp->split >= 2) {
+        if (workspace_bytes < split_bytes(dp->split, (int64_t)B * N * H)) return DFA_ERR_WORKSPACE;
+        split_ws = static_cast<float*>(workspace);
+    }
+    return launch_forward(*dp, q, k, v, sq, sk, sv, B, H, N, dt, scale, out, out_f32, lse, split_ws, stream);
+}
+
 }  // namespace
 
 extern "C" {
 
-int dfa_version(void) { return 100; }
+int dfa_version(void) { return 200; }
 
 const char* dfa_error_string(int code) {
     switch (code) {
@@ -215,6 +331,7 @@ const char* dfa_error_string(int code) {
         case DFA_ERR_ALIGN: return "pointer or stride breaks 16-byte row alignment";
         case DFA_ERR_LAUNCH: return "HIP runtime error (allocation, copy or launch)";
         case DFA_ERR_TOO_LARGE: return "problem too large for the kernel's index arithmetic";
+        case DFA_ERR_WORKSPACE: return "workspace smaller than dfa_workspace_bytes() asks for";
         default: return "unknown error code";
     }
 }
@@ -247,10 +364,10 @@ int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t* h
 int dfa_forward(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
                 dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
                 const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
-                void* out, float* lse, void* stream) {
+                void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
     try {
         return forward_impl(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets,
-                            out, dt == DFA_F32, lse, stream);
+                            out, dt == DFA_F32, lse, workspace, workspace_bytes, stream);
     } catch (const std::bad_alloc&) {
         return DFA_ERR_LAUNCH;
     }
@@ -263,7 +380,7 @@ int dfa_forward_branch(const void* q, const void* k, const void* v, dfa_strides_
     if (!lse_b) return DFA_ERR_NULL;
     try {
         return forward_impl(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, &br, 1, head_offsets,
-                            out_b, true, lse_b, stream);
+                            out_b, true, lse_b, nullptr, 0, stream);
     } catch (const std::bad_alloc&) {
         return DFA_ERR_LAUNCH;
     }
@@ -339,9 +456,10 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
             return DFA_ERR_TOO_LARGE;
     }
     try {
-        DevicePlan dp;
-        rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+        PlanRef plan;
+        rc = get_plan(B, H, N, branches, nb, head_offsets, &plan);
         if (rc != DFA_OK) return rc;
+        const DevicePlan& dp = *plan;
         BwdParams p;
         p.q = q; p.k = k; p.v = v; p.out = out; p.dout = dout;
         p.sqb = sq.b; p.sqn = sq.n; p.sqh = sq.h;
@@ -367,14 +485,18 @@ int dfa_linear(const void* x, const void* w, void* y, int64_t M, int32_t N, int3
     // lane offsets inside an 8-row group are 32-bit; tiles are counted in 32 bits
     if (ldx >= ((int64_t)1 << 26) || ldw >= ((int64_t)1 << 26) || (M / 256) * (int64_t)(N / 128) >= ((int64_t)1 << 30))
         return DFA_ERR_TOO_LARGE;
-    return launch_linear_bf16(x, w, y, M, N, K, ldx, ldw, ldy, static_cast<hipStream_t>(stream)) == hipSuccess
+    int device = 0;
+    ChipShape chip;
+    const int rc = current_chip(&device, &chip);
+    if (rc != DFA_OK) return rc;
+    return launch_linear_bf16(x, w, y, M, N, K, ldx, ldw, ldy, chip, static_cast<hipStream_t>(stream)) == hipSuccess
                ? DFA_OK : DFA_ERR_LAUNCH;
 }
 
 int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t layers,
                       int32_t B, int32_t H, int32_t N, int32_t D, float scale,
                       const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
-                      void* qkv_ws, void* attn_ws, void* y, void* stream) {
+                      void* qkv_ws, void* attn_ws, void* y, void* workspace, size_t workspace_bytes, void* stream) {
     if (!x || !w_qkv || !w_o || !qkv_ws || !attn_ws || !y) return DFA_ERR_NULL;
     if (layers < 1) return DFA_ERR_SHAPE;
     int rc = check_common(B, H, N, D, DFA_BF16);
@@ -386,13 +508,25 @@ int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t
     const uint16_t* qkv = static_cast<const uint16_t*>(qkv_ws);
     // q, k, v of token (b, n), head h live at qkv[((b*N + n)*3 + t)*E + h*D ..]
     const dfa_strides_t sq = {(int64_t)N * 3 * E, 3 * E, D};
+    // every argument error is found here, before the first launch overwrites a workspace
+    rc = check_forward_args(qkv, qkv + E, qkv + 2 * E, sq, sq, sq, B, H, N, D, DFA_BF16, scale, branches, nb,
+                            head_offsets, attn_ws, nullptr);
+    if (rc != DFA_OK) return rc;
+    for (const void* ptr : {x, w_qkv, w_o, (const void*)y})
+        if (reinterpret_cast<uintptr_t>(ptr) % 16) return DFA_ERR_ALIGN;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return DFA_ERR_ALIGN;
     try {
+        PlanRef dp;
+        rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+        if (rc != DFA_OK) return rc;
+        if (workspace && dp->split >= 2 && workspace_bytes < split_bytes(dp->split, (int64_t)B * N * H))
+            return DFA_ERR_WORKSPACE;
         for (int l = 0; l < layers; ++l) {
             rc = dfa_linear(l == 0 ? x : y, wq + (int64_t)l * 3 * E * E, qkv_ws, M, (int32_t)(3 * E), (int32_t)E,
                             E, E, 3 * E, stream);
             if (rc != DFA_OK) return rc;
-            rc = forward_impl(qkv, qkv + E, qkv + 2 * E, sq, sq, sq, B, H, N, D, DFA_BF16, scale, branches, nb,
-                              head_offsets, attn_ws, false, nullptr, stream);
+            rc = launch_forward(*dp, qkv, qkv + E, qkv + 2 * E, sq, sq, sq, B, H, N, DFA_BF16, scale, attn_ws, false,
+                                nullptr, dp->split >= 2 ? static_cast<float*>(workspace) : nullptr, stream);
             if (rc != DFA_OK) return rc;
             rc = dfa_linear(attn_ws, wo + (int64_t)l * E * E, y, M, (int32_t)E, (int32_t)E, E, E, E, stream);
             if (rc != DFA_OK) return rc;
@@ -401,6 +535,22 @@ int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t
         return DFA_ERR_LAUNCH;
     }
     return DFA_OK;
+}
+
+size_t dfa_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
+                           const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets) {
+    if (check_common(B, H, N, D, dt) != DFA_OK || check_branches(H, N, branches, nb, head_offsets) != DFA_OK) return 0;
+    if (dt != DFA_BF16) return 0;
+    try {
+        int device = 0;
+        ChipShape chip;                    // the MI355X when no device can be asked
+        if (current_chip(&device, &chip) != DFA_OK) (void)hipGetLastError();
+        HostPlan hp;
+        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, chip, &hp);
+        return split_bytes(split_factor(hp, chip), (int64_t)B * N * H);
+    } catch (const std::bad_alloc&) {
+        return 0;
+    }
 }
 
 int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
@@ -412,7 +562,7 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
     if (rc != DFA_OK) return rc;
     try {
         HostPlan hp;
-        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, &hp);
+        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, ChipShape(), &hp);
         *n_tiles = (int32_t)hp.tiles.size();
         *n_rows = (int32_t)hp.rows.size();
         *n_segs = (int32_t)hp.segs.size();
@@ -443,36 +593,36 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
 }
 
 int dfa_release_plans(void) {
-    std::lock_guard<std::mutex> lock(g_mu);
-    int rc = DFA_OK;
-    int cur = 0;
-    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
-    for (auto& kv : g_plans) {
-        if (hipSetDevice(kv.second.device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
-            hipFree(kv.second.base) != hipSuccess)
-            rc = DFA_ERR_LAUNCH;
+    std::vector<PlanRef> dropped;          // freed after the lock (each free synchronises its device)
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        for (auto& kv : g_lru) dropped.push_back(kv.second);
+        g_lru.clear();
+        g_plans.clear();
+        g_cached_bytes = 0;
     }
-    g_plans.clear();
-    if (have_cur) (void)hipSetDevice(cur);
-    return rc;
+    return DFA_OK;
 }
 
 int dfa_forward_timed(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
                       dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
                       float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
-                      void* out, float* lse, void* stream, int32_t iters, float* ms) {
+                      void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+                      int32_t iters, float* ms) {
     if (!ms) return DFA_ERR_NULL;
     if (iters < 1) return DFA_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // one untimed call builds the plan and surfaces argument errors
-    int rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse, stream);
+    int rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse,
+                         workspace, workspace_bytes, stream);
     if (rc != DFA_OK) return rc;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return DFA_ERR_LAUNCH;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return DFA_ERR_LAUNCH; }
     bool ok = hipEventRecord(e0, st) == hipSuccess;
     for (int i = 0; ok && i < iters && rc == DFA_OK; ++i)
-        rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse, stream);
+        rc = dfa_forward(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse,
+                         workspace, workspace_bytes, stream);
     ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
     float total = 0.f;
     ok = ok && hipEventElapsedTime(&total, e0, e1) == hipSuccess;

@@ -85,7 +85,7 @@ hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st);
 hipError_t launch_bwd_bf16(const BwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
-                              int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st);
+                              int64_t ldx, int64_t ldw, int64_t ldy, const ChipShape& chip, hipStream_t st);
 hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,
                             int32_t* d_idx, hipStream_t st);
 hipError_t launch_gather(const void* x, int64_t sb, int64_t sn, int64_t sh, int32_t B, int32_t H,

@@ -22,6 +22,7 @@
 // Epilogue: each wave rounds its results to bf16, lays them out row-major in its own piece of
 // LDS (the stages are free by then) and stores them 16 bytes per lane, eight lanes to a row.
 #include "dfa_device.h"
+#include "dfa_mfma.h"
 
 namespace dfa {
 
@@ -30,40 +31,12 @@ namespace {
 constexpr int kLinBM = 256;                // rows of y per workgroup
 constexpr int kLinBK = 64;                 // k elements per stage: one 128-byte LDS row
 constexpr int kLinStages = 2;
-constexpr int kLinCusPerDie = 32;          // one workgroup fits a CU at a time
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-#define DFA_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 // 16-byte chunk swizzle: chunk c of LDS row rho sits at chunk c ^ swizzle(rho).  Eight consecutive
 // rows then spread one chunk column over all 64 banks (a fragment read takes row r16 of a 16-row block).
 __device__ __forceinline__ int lin_swizzle(int rho) { return rho & 7; }
-
-template <int N>
-__device__ __forceinline__ void lin_wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_addr +
-// 16*L.  gbase and lds_addr are wave-uniform.  Inline assembly, so that the compiler's
-// wait-count insertion does not see the copy and drain it before every LDS read; the waits are
-// placed by hand.
-__device__ __forceinline__ void lin_copy16(const void* gbase, uint32_t lane_byte_offset, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(lane_byte_offset), "s"(gbase)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ const void* lin_uniform_ptr(const void* p) {
-    const uint64_t x = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
-}
 
 // The 256 x BN tile of y at (m0, n0): y[m][n] = sum_k x[m][k] * w[n][k].  lds: the workgroup's LDS (two stages
 // of a 256-row x tile and a BN-row w tile).
@@ -92,13 +65,13 @@ __device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, cons
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int row = 32 * wave + 8 * u;
-            lin_copy16(lin_uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off,
+            copy16_to_lds(uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off,
                        lds_addr + stage * kXStageBytes + row * 128);
         }
 #pragma unroll
         for (int u = 0; u < BN / 64; ++u) {
             const int row = (BN / 8) * wave + 8 * u;
-            lin_copy16(lin_uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off,
+            copy16_to_lds(uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off,
                        lds_addr + kXBytes + stage * kWStageBytes + row * 128);
         }
     };
@@ -118,7 +91,7 @@ __device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, cons
     issue(0, 0);
     for (int ks = 0; ks < n_k; ++ks) {
         const int stage = ks & 1;
-        lin_wait_vmcnt<0>();       // this wave's share of stage ks has landed
+        wait_vmcnt<0>();       // this wave's share of stage ks has landed
         __syncthreads();           // everyone's has, and everyone is done reading the other stage
         if (ks + 1 < n_k) issue(ks + 1, stage ^ 1);
         const uint16_t* xs = reinterpret_cast<const uint16_t*>(lds + stage * kXStageBytes) + x_rows * kLinBK;
@@ -176,19 +149,19 @@ __device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, cons
 }
 
 // Requires M % 256 == 0, N % BN == 0, K % 64 == 0, every row of x, w and y starting on a 16-byte boundary.
-// Workgroup i runs on die i % 8; tiles (256 x BN) are numbered band by band and dealt so that one die walks all
+// Workgroup i runs on die i % dies; tiles (256 x BN) are numbered band by band and dealt so that one die walks all
 // feature tiles of a row band before moving on (the x band is then read from memory once per die, w stays
-// in its L2).  One workgroup fits a CU at a time, so a die works its share off in rounds of 32 tiles; when
+// in its L2).  One workgroup fits a CU at a time, so a die works its share off in rounds of one tile per CU; when
 // the last round of a die would be at most half full (wide tiles only), its tiles are cut into two
 // 128-feature halves, which fill the die for a round half as long: the first `wide_per_die` workgroups of a
 // die take whole tiles, the others halves.
 template <int BN>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
-                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n, int wide_per_die) {
+                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n, int wide_per_die, int dies) {
     __shared__ __attribute__((aligned(1024))) char lds[kLinStages * (kLinBM + BN) * kLinBK * 2];
-    const int die = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
-    const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;
+    const int die = blockIdx.x % dies, local = blockIdx.x / dies;
+    const int per_die = (tiles_m * tiles_n + dies - 1) / dies;
     const bool whole = BN == 128 || local < wide_per_die;
     const int t = die * per_die + (whole ? local : wide_per_die + (local - wide_per_die) / 2);
     if (t >= tiles_m * tiles_n || (!whole && wide_per_die + (local - wide_per_die) / 2 >= per_die)) return;
@@ -199,32 +172,34 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
 
 template <int BN>
 hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
-                        int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st) {
+                        int64_t ldx, int64_t ldw, int64_t ldy, const ChipShape& chip, hipStream_t st) {
+    const int dies = chip.dies > 0 ? chip.dies : 1, cus_per_die = chip.cus / dies > 0 ? chip.cus / dies : 1;
     const int tiles_m = (int)(M / kLinBM), tiles_n = N / BN;
-    const int per_die = (tiles_m * tiles_n + kNumXcd - 1) / kNumXcd;
-    // wide tiles: whole rounds of a die's 32 CUs as they are, a last round that is at most half full in halves
-    const int rem = per_die % kLinCusPerDie;
-    const int wide_per_die = (BN == 256 && rem > 0 && 2 * rem <= kLinCusPerDie) ? per_die - rem : per_die;
+    const int per_die = (tiles_m * tiles_n + dies - 1) / dies;
+    // wide tiles: whole rounds of a die's CUs as they are, a last round that is at most half full in halves
+    const int rem = per_die % cus_per_die;
+    const int wide_per_die = (BN == 256 && rem > 0 && 2 * rem <= cus_per_die) ? per_die - rem : per_die;
     const int wg_per_die = wide_per_die + 2 * (per_die - wide_per_die);
-    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(wg_per_die * kNumXcd), dim3(512), 0, st,
+    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(wg_per_die * dies), dim3(512), 0, st,
                        static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(y),
-                       K, ldx, ldw, ldy, tiles_m, tiles_n, wide_per_die);
+                       K, ldx, ldw, ldy, tiles_m, tiles_n, wide_per_die, dies);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
-                              int64_t ldx, int64_t ldw, int64_t ldy, hipStream_t st) {
+                              int64_t ldx, int64_t ldw, int64_t ldy, const ChipShape& chip, hipStream_t st) {
     // One workgroup per CU at a time.  The 256-feature tile moves fewer bytes per flop; the 128-feature
     // tile is taken when the last round of wide tiles would leave too much of the chip idle.
     bool wide = N % 256 == 0;
     if (wide) {
-        const int64_t tiles = (M / kLinBM) * (N / 256), rounds = (tiles + 255) / 256;
-        wide = tiles * 10 >= rounds * 256 * 8;
+        const int64_t cus = chip.cus > 0 ? chip.cus : 1;
+        const int64_t tiles = (M / kLinBM) * (N / 256), rounds = (tiles + cus - 1) / cus;
+        wide = tiles * 10 >= rounds * cus * 8;
     }
-    return wide ? launch_tiles<256>(x, w, y, M, N, K, ldx, ldw, ldy, st)
-                : launch_tiles<128>(x, w, y, M, N, K, ldx, ldw, ldy, st);
+    return wide ? launch_tiles<256>(x, w, y, M, N, K, ldx, ldw, ldy, chip, st)
+                : launch_tiles<128>(x, w, y, M, N, K, ldx, ldw, ldy, chip, st);
 }
 
 }  // namespace dfa

@@ -115,7 +115,9 @@ int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, con
 }
 
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-                const int32_t* offsets, int order_mode, HostPlan* plan) {
+                const int32_t* offsets, int order_mode, const ChipShape& chip, HostPlan* plan) {
+    const int kNumXcd = std::max(chip.dies, 1);
+    const int kSlotsPerDie = std::max(chip.fwd_slots_per_die(), 1);
     plan->tiles.clear();
     plan->rows.clear();
     plan->segs.clear();
@@ -256,6 +258,17 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
     for (size_t p = 0; p < longest; ++p)
         for (int d = 0; d < kNumXcd; ++d)
             plan->items.push_back(p < per_die[d].size() ? per_die[d][p] : Item{-1, 0, Tile{0, 0, 0, 0, 0, 0}});
+}
+
+int32_t split_factor(const HostPlan& plan, const ChipShape& chip) {
+    constexpr int kMaxSplit = 4;
+    constexpr int kMinShareSteps = 8;    // a share of fewer 64-key steps is not worth a partial result and its merge
+    const int64_t slots = chip.fwd_slots(), items = (int64_t)std::max<size_t>(plan.items.size(), 1);
+    if (items * 2 > slots) return 1;
+    int64_t longest = 0;
+    for (const Tile& t : plan.tiles) longest = std::max<int64_t>(longest, t.n_steps);
+    const int64_t split = std::min<int64_t>(std::min<int64_t>(kMaxSplit, longest / kMinShareSteps), slots / items);
+    return split >= 2 ? (int32_t)split : 1;
 }
 
 }  // namespace dfa

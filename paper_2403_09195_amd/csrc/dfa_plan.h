@@ -13,8 +13,7 @@
 namespace dfa {
 
 constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
-constexpr int kNumXcd = 8;       // MI355X: 8 accelerator dies, workgroups dealt round-robin
-constexpr int kSlotsPerDie = 64;         // workgroups of the forward kernel that run at once on one die (32 CUs x 2)
+constexpr int kFwdWorkgroupsPerCu = 2;   // workgroups of the bf16 forward kernel that fit one compute unit
 constexpr int kTailItemsPerDie = 96;     // launch order: items at the end of a die's list that go heaviest first
 constexpr int kMaxTileSegs = 32; // key progressions per tile (the kernels hold a tile's list in LDS)
 constexpr int kMaxCoalesceLcm = 64;   // largest common period of a tile's dilation rates that is coalesced
@@ -42,6 +41,15 @@ struct Item {        // one workgroup of the launch
     Tile t;          // copy of tiles[tile]: a workgroup reads what it needs to start in one load
 };
 
+// What the planner needs to know of the chip: workgroup i of a launch runs on die i mod dies (each
+// die has its own L2).  The library reads both numbers from the device; the default is the MI355X.
+struct ChipShape {
+    int32_t dies = 8;
+    int32_t cus = 256;
+    int32_t fwd_slots() const { return cus * kFwdWorkgroupsPerCu; }          // forward workgroups resident at once
+    int32_t fwd_slots_per_die() const { return fwd_slots() / (dies > 0 ? dies : 1); }
+};
+
 struct HostPlan {
     std::vector<Tile> tiles;
     std::vector<int32_t> rows;
@@ -61,6 +69,11 @@ inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t
 // Builds tiles, row lists, key segments and the launch order for B images.
 // order_mode: 3 = default (see dfa_plan.cpp), 0 to 2 are alternatives kept for measurement.
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-                const int32_t* offsets, int order_mode, HostPlan* plan);
+                const int32_t* offsets, int order_mode, const ChipShape& chip, HostPlan* plan);
+
+// Launches of the bf16 forward kernel with fewer workgroups than the chip has slots walk every tile with
+// several workgroups, each over a share of its 64-key steps, into fp32 partial results that a merge launch
+// combines.  Returns the number of shares per tile (1 = no split) for a built plan.
+int32_t split_factor(const HostPlan& plan, const ChipShape& chip);
 
 }  // namespace dfa

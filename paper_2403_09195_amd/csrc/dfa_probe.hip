@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/dfa.h"
+#include "../../include/dfa_bench.h"
 #include "dfa_device.h"
 
 namespace dfa {

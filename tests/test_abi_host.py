@@ -22,15 +22,17 @@ def B():
 
 
 def test_library_exports_every_declared_symbol(B):
-    header = open(os.path.join(ROOT, "include", "dfa.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(dfa_[a-z_]+)\s*\(", header))
-    assert declared == set(B.EXPORTS)
     raw = ctypes.CDLL(os.path.join(ROOT, "paper_2403_09195_amd", "libdfa.so"))
-    for name in declared:
-        assert hasattr(raw, name), name
-    assert B.version() >= 100
-    for code in range(0, -8, -1):
+    for fname, names in (("dfa.h", B.EXPORTS), ("dfa_bench.h", B.BENCH_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared = set(re.findall(r"\b(dfa_[a-z_]+)\s*\(", header))
+        assert declared == set(names), fname
+        for name in declared:
+            assert hasattr(raw, name), name
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["dfa.h", "dfa_bench.h"]
+    assert B.version() >= 200
+    for code in range(0, -9, -1):
         assert B.error_string(code) != "unknown error code"
     assert B.error_string(-99) == "unknown error code"
 
@@ -55,7 +57,7 @@ def _fwd_rc(mod, **kw):
     vp = ctypes.c_void_p
     return mod.lib().dfa_forward(vp(a["q"]), vp(a["k"]), vp(a["v"]), st, st, st, a["Bsz"], a["H"], a["N"], a["D"],
                                a["dt"], ctypes.c_float(a["scale"]), br, nb, mod._i32_array(a["offs"]),
-                               vp(a["out"]), vp(a["lse"]), None)
+                               vp(a["out"]), vp(a["lse"]), vp(a.get("ws")), ctypes.c_size_t(a.get("ws_bytes", 0)), None)
 
 
 def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
@@ -72,7 +74,22 @@ def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
     assert _fwd_rc(B, branches=[(16, 1)] * 9) == -3
     assert _fwd_rc(B, dt=7) == -4
     assert _fwd_rc(B, q=0x10004) == -5
+    assert _fwd_rc(B, ws=0x60004, ws_bytes=1 << 20) == -5   # misaligned workspace
     assert _fwd_rc(B, sq=B.Strides(64 * 2 * 64, 2 * 64 + 4, 64)) == -5
+
+
+def test_workspace_bytes_follows_the_split_rule(B):
+    """Room for the fp32 partial results (out and lse) of every share of a split launch: the single-image
+    workload has 192 tiles for 512 workgroup slots, so two workgroups walk each tile; the batch of 16 fills
+    the chip and needs none.  (Without a device the library assumes the MI355X's 256 compute units.)"""
+    wl = [(1024, 1), (2048, 2), (4096, 4)]
+    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, wl) == 2 * 4096 * 12 * 65 * 4
+    assert B.workspace_bytes(16, 12, 4096, 64, B.DFA_BF16, wl) == 0
+    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_F32, wl) == 0
+    assert B.workspace_bytes(1, 12, 4096, 128, B.DFA_BF16, wl) == 0          # D the library does not take
+    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, [(1024, 0)]) == 0   # r < 1
+    # walks too short to share (fewer than 16 steps of 64 keys): no split however few the tiles
+    assert B.workspace_bytes(1, 2, 512, 64, B.DFA_BF16, [(512, 1)]) == 0
 
 
 def test_stage_entry_points_reject_bad_arguments_before_any_gpu_work(B):

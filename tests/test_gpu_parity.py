@@ -1,12 +1,13 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
 seeded inputs.  Bars: index maps and byte movement bit-exact; bf16 outputs max-abs <= 2e-2 and
-mean-abs <= 2e-3; fp32 outputs max-abs <= 1e-5; lse (no bar given by the workload definition)
-<= 3.95e-3 for bf16 (derived in gpu_util.BF16_LSE) and 1e-5 * max(1, |lse|) for fp32, with -inf matching
-exactly."""
+mean-abs <= 2e-3; fp32 outputs max-abs <= 1e-5; lse (no bar given by the workload definition):
+bf16 per row from the arithmetic (gpu_util.bf16_lse_bar: about 1e-3 on the workloads' rows, never more than the
+worst case 3.95e-3, which alone applies to inputs with equal or hand-made scores), fp32 1e-5 * max(1, |lse|),
+with -inf matching exactly."""
 import numpy as np
 import pytest
 
-from gpu_util import BF16_LSE, check_lse, error_stats, make_qkv, to_device, to_f64
+from gpu_util import BF16_LSE, check_lse, check_lse_bf16, error_stats, make_qkv, to_device, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -22,10 +23,15 @@ def B():
     return binding
 
 
-def _check_bf16(out, lse, o_ref, l_ref, tag=""):
+def _check_bf16(out, lse, o_ref, l_ref, tag="", rows=None):
+    """rows = (oracle, ex, branches, scale, head_offsets) of a problem on random data: lse is then held to the
+    per-row bar; without it to the worst-case bar."""
     mx, mean = error_stats(to_f64(out), o_ref)
-    le = check_lse(to_f64(lse), l_ref, atol=BF16_LSE)
-    print(f"[{tag}] bf16 out max-abs {mx:.3e} mean-abs {mean:.3e} lse max-abs {le:.3e}", flush=True)
+    if rows is None:
+        le, frac = check_lse(to_f64(lse), l_ref, atol=BF16_LSE), float("nan")
+    else:
+        le, frac = check_lse_bf16(to_f64(lse), rows[0], rows[1], rows[2], rows[3], l_ref, rows[4])
+    print(f"[{tag}] bf16 out max-abs {mx:.3e} mean-abs {mean:.3e} lse max-abs {le:.3e} (at most {frac:.2f} of a row's bar)", flush=True)
     assert mx <= BF16_MAX and mean <= BF16_MEAN
     return mx, mean
 
@@ -108,11 +114,8 @@ def test_fp32_multi_branch_ragged(B, oracle, scale):
     (q, k, v), ex = make_qkv(101, Bsz, N, H, D, "f32")
     out, lse = B.forward(q, k, v, branches, scale, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, scale, head_offsets=offs)
-    # scale = 1 is the literal Eq. 2: logits are 8x larger (sigma 8, row maxima 30-40), and so
-    # is the absolute fp32 rounding error of each logit, which the exponential turns into a
-    # relative error of the weights: the 1e-5 bar of the 1/sqrt(D) convention scales to 8e-5;
-    # 3e-5 is asserted.
-    _check_f32(out, lse, o_ref, l_ref, f"f32 ragged s={scale}", tol=1e-5 if scale < 1.0 else 3e-5)
+    # scale = 1 is the literal Eq. 2 (logits 8x larger: sigma 8, row maxima 30-40); the same 1e-5 bar
+    _check_f32(out, lse, o_ref, l_ref, f"f32 ragged s={scale}")
 
 
 # ---------------------------------------------------------------- bf16 path
@@ -122,7 +125,7 @@ def test_bf16_small_multi_tile(B, oracle):
     (q, k, v), ex = make_qkv(102, Bsz, N, H, D, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, "bf16 small")
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 small", rows=(oracle, ex, branches, 0.125, None))
     out2, lse2 = B.forward(q, k, v, branches, 0.125)
     assert bool((out2 == out).all()) and bool((lse2 == lse).all())
 
@@ -134,7 +137,7 @@ def test_bf16_ragged_tiles_explicit_offsets_and_uncovered_rows(B, oracle):
     (q, k, v), ex = make_qkv(103, Bsz, N, H, D, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
-    _check_bf16(out, lse, o_ref, l_ref, "bf16 ragged")
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 ragged", rows=(oracle, ex, branches, 0.125, offs))
     dead = np.isneginf(l_ref).transpose(0, 2, 1)                     # [B, N, H]
     assert dead.any() and np.all(to_f64(out)[dead] == 0.0)
 
@@ -144,7 +147,7 @@ def test_bf16_dense_special_case_and_single_head(B, oracle):
     (q, k, v), ex = make_qkv(104, 1, 320, 1, 64, "bf16")
     out, lse = B.forward(q, k, v, [(320, 1)], 0.125)
     o_ref, l_ref = oracle.forward(*ex, [(320, 1)], 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, "bf16 dense")
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 dense", rows=(oracle, ex, [(320, 1)], 0.125, None))
 
 
 def test_bf16_eight_branches_and_no_lse(B, oracle):
@@ -153,7 +156,7 @@ def test_bf16_eight_branches_and_no_lse(B, oracle):
     (q, k, v), ex = make_qkv(105, Bsz, N, H, D, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, "bf16 8 branches")
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 8 branches", rows=(oracle, ex, branches, 0.125, None))
     out2, none = B.forward(q, k, v, branches, 0.125, want_lse=False)
     assert none is None and bool((out2 == out).all())
 
@@ -170,10 +173,10 @@ def test_bf16_key_counts_around_the_pipeline_beats(B, oracle, count, r):
     (q, k, v), ex = make_qkv(300 + count, 2, N, H, 64, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, f"bf16 count {count} r {r}")
+    _check_bf16(out, lse, o_ref, l_ref, f"bf16 count {count} r {r}", rows=(oracle, ex, branches, 0.125, None))
     out1, lse1 = B.forward(q, k, v, branches[:1], 0.125)
     o1, l1 = oracle.forward(*ex, branches[:1], 0.125)
-    _check_bf16(out1, lse1, o1, l1, f"bf16 count {count} r {r}, one branch")
+    _check_bf16(out1, lse1, o1, l1, f"bf16 count {count} r {r}, one branch", rows=(oracle, ex, branches[:1], 0.125, None))
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -190,7 +193,7 @@ def test_ragged_partitions(B, oracle, dtype, N, branches, offs):
     out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
     if dtype == "bf16":
-        _check_bf16(out, lse, o_ref, l_ref, f"ragged N={N}")
+        _check_bf16(out, lse, o_ref, l_ref, f"ragged N={N}", rows=(oracle, ex, branches, 0.125, offs))
     else:
         _check_f32(out, lse, o_ref, l_ref, f"ragged N={N}")
     dead = np.isneginf(l_ref).transpose(0, 2, 1)
@@ -214,7 +217,7 @@ def test_keys_kept_by_several_branches(B, oracle, dtype, N, branches, offs):
     out, lse = B.forward(q, k, v, branches, 0.125, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
     if dtype == "bf16":
-        _check_bf16(out, lse, o_ref, l_ref, f"shared keys N={N}")
+        _check_bf16(out, lse, o_ref, l_ref, f"shared keys N={N}", rows=(oracle, ex, branches, 0.125, offs))
     else:
         _check_f32(out, lse, o_ref, l_ref, f"shared keys N={N}")
 
@@ -255,7 +258,7 @@ def test_bf16_side_stream_and_plan_release(B, oracle):
     (q, k, v), ex = make_qkv(302, Bsz, N, H, D, "bf16")
     out0, lse0 = B.forward(q, k, v, branches, 0.125)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
-    _check_bf16(out0, lse0, o_ref, l_ref, "default stream")
+    _check_bf16(out0, lse0, o_ref, l_ref, "default stream", rows=(oracle, ex, branches, 0.125, None))
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -270,7 +273,7 @@ def test_bf16_side_stream_and_plan_release(B, oracle):
     (q3, k3, v3), ex3 = make_qkv(303, 1, 256, 2, D, "bf16")
     out3, lse3 = B.forward(q3, k3, v3, [(128, 2)], 0.125)
     o3, l3 = oracle.forward(*ex3, [(128, 2)], 0.125)
-    _check_bf16(out3, lse3, o3, l3, "second shape")
+    _check_bf16(out3, lse3, o3, l3, "second shape", rows=(oracle, ex3, [(128, 2)], 0.125, None))
     out4, _ = B.forward(q, k, v, branches, 0.125)
     assert bool((out4 == out0).all())
 
@@ -288,10 +291,13 @@ def test_forward_and_backward_replay_from_a_captured_graph(B, Bsz, N, H):
     g = to_device(synth.tensor(900, 7, (Bsz, N, H, 64), "bf16")[0])
     out, lse = B.forward(q, k, v, branches, 0.125)                     # builds the plan
     dq, dk, dv = B.backward(q, k, v, out, lse, g, branches, 0.125)
+    need = B.workspace_bytes(Bsz, H, N, 64, B.DFA_BF16, branches)
+    assert (need > 0) == (Bsz == 1)
+    ws = torch.empty((max(need, 16),), dtype=torch.uint8, device="cuda")   # the caller's workspace: allocated before the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        B.forward(q, k, v, branches, 0.125, out=out, lse=lse)
+        B.forward(q, k, v, branches, 0.125, out=out, lse=lse, workspace=ws)
         grads = B.backward(q, k, v, out, lse, g, branches, 0.125)
     for rep in range(3):
         nq, nk, nv = mk(901 + rep)
@@ -317,7 +323,7 @@ def test_bf16_reads_packed_qkv_through_strides(B, oracle):
     packed = to_device(st)
     out, lse = B.forward(packed[:, :, 0], packed[:, :, 1], packed[:, :, 2], branches, 0.125)
     o_ref, l_ref = oracle.forward(ex[:, :, 0], ex[:, :, 1], ex[:, :, 2], branches, 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, "bf16 packed qkv")
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 packed qkv", rows=(oracle, (ex[:, :, 0], ex[:, :, 1], ex[:, :, 2]), branches, 0.125, None))
 
 
 def test_bf16_sam_scale_config_full(B, oracle):
@@ -326,7 +332,7 @@ def test_bf16_sam_scale_config_full(B, oracle):
     (q, k, v), ex = make_qkv(c["seed"], c["B"], c["N"], c["H"], c["D"], "bf16")
     out, lse = B.forward(q, k, v, c["branches"], 0.125)
     o_ref, l_ref = oracle.forward(*ex, c["branches"], 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, "sam-scale B=1")
+    _check_bf16(out, lse, o_ref, l_ref, "sam-scale B=1", rows=(oracle, ex, c["branches"], 0.125, None))
 
 
 @pytest.mark.parametrize("name", ["throughput", "highres"])
@@ -338,7 +344,7 @@ def test_bf16_full_size_configs_element_by_element(B, oracle, name):
     (q, k, v), ex = make_qkv(c["seed"], c["B"], c["N"], c["H"], c["D"], "bf16")
     out, lse = B.forward(q, k, v, c["branches"], 0.125)
     o_ref, l_ref = oracle.forward(*ex, c["branches"], 0.125)
-    _check_bf16(out, lse, o_ref, l_ref, f"{name}, every element")
+    _check_bf16(out, lse, o_ref, l_ref, f"{name}, every element", rows=(oracle, ex, c["branches"], 0.125, None))
 
 
 def _branch_membership(N, H, branches):
@@ -441,7 +447,10 @@ def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
         ob, lb = B.forward_branch(q, k, v, w, r, 0.125)
         assert ob.dtype == torch.float32
         mx, mean = error_stats(to_f64(ob), bo_ref[x])
-        check_lse(to_f64(lb), bl_ref[x], atol=BF16_LSE if dtype == "bf16" else 1e-5, rtol=0 if dtype == "bf16" else 1e-5)
+        if dtype == "bf16":
+            check_lse_bf16(to_f64(lb), oracle, ex, [(w, r)], 0.125, bl_ref[x])
+        else:
+            check_lse(to_f64(lb), bl_ref[x], atol=1e-5, rtol=1e-5)
         assert mx <= (BF16_MAX if dtype == "bf16" else F32_MAX)
         dead = np.isneginf(bl_ref[x]).transpose(0, 2, 1)
         assert np.all(to_f64(ob)[dead] == 0.0)
@@ -450,7 +459,7 @@ def test_unmerged_branches_and_standalone_merge(B, oracle, dtype):
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     out, lse = B.merge(torch.stack(outs), torch.stack(lses), tdt)
     if dtype == "bf16":
-        _check_bf16(out, lse, o_ref, l_ref, "branch+merge bf16")
+        _check_bf16(out, lse, o_ref, l_ref, "branch+merge bf16", rows=(oracle, ex, branches, 0.125, None))
     else:
         _check_f32(out, lse, o_ref, l_ref, "branch+merge f32")
     # the merge kernel alone, on the oracle's own fp64 branch results rounded to fp32

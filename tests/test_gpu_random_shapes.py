@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import helpers
-from gpu_util import BF16_LSE, check_lse, error_stats, make_qkv, to_device, to_f64
+from gpu_util import check_lse, check_lse_bf16, error_stats, make_qkv, to_device, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +43,7 @@ def test_random_problem_forward_and_backward(B, oracle, seed):
         o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
         mx, mean = error_stats(to_f64(out), o_ref)
         if dtype == "bf16":
-            check_lse(to_f64(lse), l_ref, atol=BF16_LSE)
+            check_lse_bf16(to_f64(lse), oracle, ex, branches, 0.125, l_ref, offs)     # per-row bar
             assert mx <= 2e-2 and mean <= 2e-3
         else:
             check_lse(to_f64(lse), l_ref, atol=1e-5, rtol=1e-5)
@@ -103,7 +103,7 @@ def test_random_problem_with_many_branches_forward(B, oracle, seed):
         o_ref, l_ref = oracle.forward(*ex, branches, 0.125, head_offsets=offs)
         mx, mean = error_stats(to_f64(out), o_ref)
         if dtype == "bf16":
-            check_lse(to_f64(lse), l_ref, atol=BF16_LSE)
+            check_lse_bf16(to_f64(lse), oracle, ex, branches, 0.125, l_ref, offs)     # per-row bar
             assert mx <= 2e-2 and mean <= 2e-3
         else:
             check_lse(to_f64(lse), l_ref, atol=1e-5, rtol=1e-5)
@@ -121,7 +121,8 @@ def test_random_problem_with_sharp_softmax_bf16(B, oracle, seed):
     (q, k, v), ex = make_qkv(2000 + seed, Bsz, N, H, 64, "bf16")
     out, lse = B.forward(q, k, v, branches, 1.0, head_offsets=offs)
     o_ref, l_ref = oracle.forward(*ex, branches, 1.0, head_offsets=offs)
-    le = check_lse(to_f64(lse), l_ref, atol=BF16_LSE, rtol=1e-6)
+    # few keys carry a row here: the per-row bar is at or near the worst case for most rows
+    le, _ = check_lse_bf16(to_f64(lse), oracle, ex, branches, 1.0, l_ref, offs)
     d = np.abs(to_f64(out) - o_ref)
     print(f"[sharp {seed}] lse max-abs {le:.3e} out max-abs {d.max():.3e}", flush=True)
     assert np.all(d <= 2.0 ** -7 * np.maximum(1.0, np.abs(o_ref)))

@@ -149,7 +149,7 @@ def test_three_layer_stack_end_to_end(B, oracle):
     print(f"[stack x{layers}] rel max {mx:.3e} mean {mean:.3e}, result rms {np.sqrt(np.mean(ref ** 2)):.3e}", flush=True)
     assert mx <= 0.15 and mean <= 2e-2
     ws = (torch.empty_like(qkv), torch.empty_like(attn), torch.empty_like(y))
-    y2, _, _ = B.encoder_stack(x, wq, wo, H, branches, 0.125, workspace=ws)
+    y2, _, _ = B.encoder_stack(x, wq, wo, H, branches, 0.125, buffers=ws)
     assert y2 is ws[2] and bool((y2 == y).all())
 
 
