@@ -140,6 +140,26 @@ int dfa_forward(const void *q, const void *k, const void *v,
                 void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dfa_forward for callers that cannot allocate device memory (code under HIP graph capture set-up rules,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same kernels
+ * and same results as dfa_forward with a workspace, but it never calls hipMalloc / hipFree or anything else
+ * that allocates device memory.  The launch plan and the partial results of a split launch live in a static
+ * device array of DFA_STATIC_SCRATCH_BYTES (40 MiB) that each GPU the entry point runs on holds until the
+ * process ends; a shape whose plan and partial results do not fit returns DFA_ERR_WORKSPACE before anything
+ * is enqueued (every shape that is split fits; the limit is met by plans of some 700 000 workgroups).
+ * The first call with a shape other than the previous call's on that GPU synchronises the device and copies
+ * the new plan in (not capturable; call once before capturing); calls that repeat the shape only enqueue.
+ * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race on it
+ * and must be serialised by the caller.
+ */
+#define DFA_STATIC_SCRATCH_BYTES ((size_t)40 << 20)
+int dfa_forward_static(const void *q, const void *k, const void *v,
+                       dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                       int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                       const dfa_branch_t *branches, int32_t nb, const int32_t *head_offsets,
+                       void *out, float *lse, void *stream);
+
+/*
  * Backward of dfa_forward: gradients with respect to q, k, v for a gradient dout of the merged
  * output (lse takes no gradient).  The paper gives no backward pass; this is the chain rule on
  * Eq. 2 and the branch merge: with P = exp(scale q_n.k_j - lse_n) per (branch, n, j) pair of

@@ -19,6 +19,7 @@ DFA_ERR_WORKSPACE = -8
 # include/dfa.h (the operator) and include/dfa_bench.h (measurement aids)
 EXPORTS = [
     "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_workspace_bytes", "dfa_forward",
+    "dfa_forward_static",
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
     "dfa_release_plans", "dfa_linear", "dfa_encoder_stack", "dfa_backward",
 ]
@@ -73,6 +74,7 @@ def lib():
                ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp, ctypes.c_size_t, vp]
         L.dfa_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int, ctypes.POINTER(Branch), i32, _i32p]
         L.dfa_forward.argtypes = fwd
+        L.dfa_forward_static.argtypes = fwd[:-3] + [vp]
         L.dfa_forward_timed.argtypes = fwd + [i32, ctypes.POINTER(f32)]
         L.dfa_forward_branch.argtypes = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32,
                                          ctypes.c_int, f32, Branch, _i32p, vp, vp, vp]
@@ -222,6 +224,20 @@ def forward(q, k, v, branches, scale, head_offsets=None, out=None, lse=None, wan
     _check(lib().dfa_forward(*args), "dfa_forward")
     if keep is not None and hasattr(keep, "record_stream"):
         keep.record_stream(torch.cuda.current_stream())     # the launch reads it after this function returns
+    return out, lse
+
+
+def forward_static(q, k, v, branches, scale, head_offsets=None, out=None, lse=None):
+    """dfa_forward_static: the forward pass through the library's static scratch array (no device allocation
+    inside the library; `out` and `lse` are the caller's)."""
+    import torch
+    B, N, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    args, _ = _fwd_args(q, k, v, branches, scale, head_offsets, out, lse, None)
+    _check(lib().dfa_forward_static(*(args[:-3] + args[-1:])), "dfa_forward_static")
     return out, lse
 
 

@@ -16,6 +16,13 @@
 #include "dfa_device.h"
 #include "dfa_plan.h"
 
+// Scratch memory of dfa_forward_static, the entry point for callers that cannot allocate: the launch plan
+// of the shape last used on this device, followed by the fp32 partial results of a split launch.  One copy
+// per GPU, held until the process ends.  Host code never uses this name as an address: the device address
+// of each GPU's copy comes from hipGetSymbolAddress, taken in dfa_forward_static with that GPU current.
+constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 using namespace dfa;
@@ -244,6 +251,17 @@ int make_offsets(const int32_t* head_offsets, int32_t H, int32_t r, HeadOffsets*
     return DFA_OK;
 }
 
+// Per-device state of dfa_forward_static: where this GPU's copy of `scratch` lives and which plan it holds.
+struct StaticScratch {
+    unsigned char* ptr = nullptr;      // from hipGetSymbolAddress with this device current
+    bool holds_plan = false;
+    PlanKey key;
+    DevicePlan plan;                   // points into ptr, not owned
+    size_t plan_bytes = 0;             // 256-byte aligned; the split partial results follow
+};
+std::mutex g_static_mu;
+std::map<int, StaticScratch> g_static;
+
 // Argument checks of the attention entry points (everything that can be found without the GPU).
 int check_forward_args(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
                        dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
@@ -368,6 +386,60 @@ int dfa_forward(const void* q, const void* k, const void* v, dfa_strides_t sq, d
     try {
         return forward_impl(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets,
                             out, dt == DFA_F32, lse, workspace, workspace_bytes, stream);
+    } catch (const std::bad_alloc&) {
+        return DFA_ERR_LAUNCH;
+    }
+}
+
+int dfa_forward_static(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                       dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt, float scale,
+                       const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,
+                       void* out, float* lse, void* stream) {
+    int rc = check_forward_args(q, k, v, sq, sk, sv, B, H, N, D, dt, scale, branches, nb, head_offsets, out, lse);
+    if (rc != DFA_OK) return rc;
+    try {
+        int device = 0;
+        ChipShape chip;
+        rc = current_chip(&device, &chip);
+        if (rc != DFA_OK) return rc;
+        // held until the launches are enqueued: two host threads must not repoint the scratch under each other
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        StaticScratch& ss = g_static[device];
+        if (!ss.ptr) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return DFA_ERR_LAUNCH;
+            }
+            ss.ptr = static_cast<unsigned char*>(p);
+            ss.plan.owned = false;
+        }
+        PlanKey key = plan_key(device, B, H, N, branches, nb, head_offsets);
+        if (!ss.holds_plan || ss.key != key) {
+            PackedPlan pp;
+            rc = pack_plan(B, H, N, branches, nb, head_offsets, chip, &pp);
+            if (rc != DFA_OK) return rc;
+            const size_t plan_bytes = align256(pp.bytes.size());
+            const size_t part_bytes = dt == DFA_BF16 ? split_bytes(pp.split, (int64_t)B * N * H) : 0;
+            if (plan_bytes + part_bytes > kStaticScratchBytes) return DFA_ERR_WORKSPACE;
+            // launches of earlier calls may still be reading the plan that is about to be overwritten
+            ss.holds_plan = false;
+            if (hipDeviceSynchronize() != hipSuccess ||
+                hipMemcpy(ss.ptr, pp.bytes.data(), pp.bytes.size(), hipMemcpyHostToDevice) != hipSuccess) {
+                (void)hipGetLastError();
+                return DFA_ERR_LAUNCH;
+            }
+            point_plan(&ss.plan, ss.ptr, pp, device);
+            ss.plan_bytes = plan_bytes;
+            ss.key = std::move(key);
+            ss.holds_plan = true;
+        } else if (dt == DFA_BF16 && ss.plan_bytes + split_bytes(ss.plan.split, (int64_t)B * N * H) > kStaticScratchBytes) {
+            return DFA_ERR_WORKSPACE;      // the plan was left by a call in the other precision, which needs no partial results
+        }
+        // the partial results of a split launch are written in full by that launch before its merge reads them:
+        // nothing in the scratch has to start at zero
+        float* split_ws = ss.plan.split >= 2 ? reinterpret_cast<float*>(ss.ptr + ss.plan_bytes) : nullptr;
+        return launch_forward(ss.plan, q, k, v, sq, sk, sv, B, H, N, dt, scale, out, dt == DFA_F32, lse, split_ws, stream);
     } catch (const std::bad_alloc&) {
         return DFA_ERR_LAUNCH;
     }
