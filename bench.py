@@ -19,12 +19,81 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
 WORKLOAD = "throughput"
-# HBM bytes per launch of the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by
-# the copy-kernel calibration (profiles/dfa_fwd_bf16_throughput.md); None for other workloads
-MEASURED_HBM_TRAFFIC_BYTES = {"throughput": 557848500}
+# HBM bytes per launch, from the counter runs: rocprofv3 FETCH_SIZE and WRITE_SIZE per dispatch, scaled by what the
+# same counters read for a plain copy of known size.  `bench.py --write-traffic <dir>` writes this file from
+# the four counter runs; the default line reads it (null when the workload has no entry).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "dfa_fwd_hbm_traffic.txt")
+# Launches back to back before anything is timed.  At the start of a burst of launches the chip runs the
+# first four or so at full speed, then drops its clock for some twenty launches and comes back to a steady
+# value after about a hundred (30 ms); any idle gap of a few milliseconds starts this over (per-launch HIP-event
+# times, profiles/dfa_fwd_bf16_throughput.md).  The workload asks for steady-state throughput, so every timed
+# region is preceded by this many milliseconds of untimed launches; the line says how many that was.
+SETTLE_MS = 150.0
 
 
 HBM_PEAK_GBS = 8000.0               # MI355X HBM3E (published)
+
+
+def settle(torch, fn, ms=SETTLE_MS):
+    """Runs fn back to back for about `ms` milliseconds (at least 20 calls), untimed; returns the number of calls."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    per_call = max((time.perf_counter() - t0) / 5, 1e-6)
+    n = int(min(max(ms * 1e-3 / per_call, 20), 20000))
+    for _ in range(n):
+        fn()
+    return n + 5
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of `workload` from TRAFFIC_FILE (lines: workload=<name> ... traffic_bytes=<n>), or None."""
+    try:
+        for ln in open(TRAFFIC_FILE):
+            kv = dict(tok.split("=", 1) for tok in ln.split() if "=" in tok)
+            if kv.get("workload") == workload and "traffic_bytes" in kv:
+                return int(kv["traffic_bytes"])
+    except OSError:
+        pass
+    return None
+
+
+def write_traffic(dirname):
+    """Reads the counter runs under `dirname` (sub-folders <workload>_fetch, <workload>_write, copy_fetch,
+    copy_write, each holding rocprofv3's *counter_collection.csv) and rewrites TRAFFIC_FILE."""
+    import csv
+    import glob
+
+    def mean_counter(sub, counter, kernel_part):
+        vals = []
+        for path in glob.glob(os.path.join(dirname, sub, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(path)):
+                if row["Counter_Name"] == counter and kernel_part in row["Kernel_Name"]:
+                    vals.append(float(row["Counter_Value"]))
+        if not vals:
+            raise SystemExit(f"bench.py: no {counter} rows for {kernel_part} under {dirname}/{sub}")
+        return sum(vals) / len(vals), len(vals)
+
+    copy_kib = (1 << 28) / 1024.0                     # --copy-calibration copies 256 MiB each way
+    f_copy, _ = mean_counter("copy_fetch", "FETCH_SIZE", "opy")
+    w_copy, _ = mean_counter("copy_write", "WRITE_SIZE", "opy")
+    f_fac, w_fac = copy_kib / f_copy, copy_kib / w_copy
+    lines = ["# HBM traffic per launch of dfa_fwd_bf16_kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, mean over the",
+             "# dispatches of one run), scaled by what the same counters read for a 256 MiB device-to-device copy.",
+             "# Written by `python3 bench.py --write-traffic <dir>`; read by bench.py for roofline.traffic.",
+             f"copy_calibration FETCH_SIZE_KiB={f_copy:.0f} WRITE_SIZE_KiB={w_copy:.0f} fetch_factor={f_fac:.4f} write_factor={w_fac:.4f}"]
+    for sub in sorted(os.listdir(dirname)):
+        if sub.endswith("_fetch") and sub != "copy_fetch":
+            wl = sub[:-len("_fetch")]
+            f, nf = mean_counter(sub, "FETCH_SIZE", "dfa_fwd")
+            w, nw = mean_counter(wl + "_write", "WRITE_SIZE", "dfa_fwd")
+            total = int(round((f * f_fac + w * w_fac) * 1024))
+            lines.append(f"workload={wl} FETCH_SIZE_KiB={f:.0f} WRITE_SIZE_KiB={w:.0f} dispatches={nf} "
+                         f"read_bytes={int(f * f_fac * 1024)} written_bytes={int(w * w_fac * 1024)} traffic_bytes={total}")
+    open(TRAFFIC_FILE, "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
 
 
 def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
@@ -38,6 +107,7 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
     esize = q.element_size()
 
     def timed(fn):
+        settle(torch, fn, 60.0)
         for _ in range(warmup):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -88,7 +158,7 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
 
 
 def sweep_report(binding, synth, torch, np, steps, warmup):
-    """Section 4.4's ablation as a synthetic sweep: image sizes 256^2, 512^2, 1024^2 (N = 256, 1024, 4096
+    """Section 4.3's ablation (Fig. 4) as a synthetic sweep: image sizes 256^2, 512^2, 1024^2 (N = 256, 1024, 4096
     tokens of 16 x 16 patches), embed 384 (6 heads) and 768 (12 heads), B = 16.  For each shape the three
     dilated branches scaled to it ((N/4, 1), (N/2, 2), (N, 4)) against dense attention over all N tokens,
     both through dfa_forward (dense = one branch with w = N, r = 1)."""
@@ -103,8 +173,7 @@ def sweep_report(binding, synth, torch, np, steps, warmup):
             dil = [(N // 4, 1), (N // 2, 2), (N, 4)]
             res = {"image": f"{int(N ** 0.5) * 16}^2", "N": N, "H": H, "B": Bsz}
             for name, br in (("dilated", dil), ("dense", [(N, 1)])):
-                for _ in range(max(warmup, 3)):
-                    binding.forward(q, k, v, br, scale, out=out, lse=lse)
+                settle(torch, lambda: binding.forward(q, k, v, br, scale, out=out, lse=lse), 60.0)
                 ms = binding.forward_timed(q, k, v, br, scale, max(steps // 4, 10), out=out, lse=lse)
                 fl = synth.useful_flops(Bsz, H, N, D, br)
                 res[name] = {"us": ms * 1e3, "useful_TFLOP/s": fl / ms / 1e9, "flops": fl}
@@ -127,8 +196,7 @@ def tile_cost_report(binding, synth, torch, np):
         lse = torch.empty((Bsz, H, N), dtype=torch.float32, device="cuda")
         for w in (256, 512, 1024, 2048, 4096):
             br = [(w, 1)]
-            for _ in range(3):
-                binding.forward(q, k, v, br, scale, out=out, lse=lse)
+            settle(torch, lambda: binding.forward(q, k, v, br, scale, out=out, lse=lse), 60.0)
             us = 1e3 * min(binding.forward_timed(q, k, v, br, scale, 30, out=out, lse=lse) for _ in range(3))
             per_slot = Bsz * H * (N // 256) / 512.0
             rows.append({"B": Bsz, "w": w, "steps_per_tile": w // 64, "tiles_per_slot": per_slot, "launch_us": us})
@@ -164,6 +232,7 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
     def run():
         return binding.encoder_stack(x, wq, wo, H, branches, scale, buffers=ws)
 
+    n_settle = settle(torch, run)
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
@@ -178,8 +247,7 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
     flops = layers * (fl_attn + fl_qkv + fl_out)
 
     def timed(fn, it=50):
-        for _ in range(5):
-            fn()
+        settle(torch, fn, 60.0)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -209,6 +277,7 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
     return {
         "metric": f"us per 1024x1024 image, all {layers} layers of the encoder attention stack", "value": wall * 1e6 / Bsz,
         "unit": "us/image", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall * 1e3,
+        "settle": {"untimed_steps_before_warmup": n_settle},
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"stack: {layers} layers, embed {E}, H={H} D={D}, B={Bsz}, N={N}, branches={branches}, "
                                "QKV projection + dilated attention + output projection per layer"},
@@ -224,11 +293,13 @@ def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None,
-                    help="timed steps (default: 2000 for the default line, about 0.6 s of launches back to back, so that the "
-                         "fixed cost of starting and draining the queue, about 1.4 ms, does not weigh on the per-step figure; "
-                         "200 for the other reports)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: 50 and 20)")
+    ap.add_argument("--steps", type=int, default=200, help="timed steps (default 200)")
+    ap.add_argument("--warmup", type=int, default=20, help="untimed steps directly before them (default 20)")
+    ap.add_argument("--settle-ms", type=float, default=SETTLE_MS,
+                    help="milliseconds of untimed launches back to back before the warm-up steps, so that the timed steps "
+                         "run at the chip's steady clock (default %(default)s; 0 times a cold burst)")
+    ap.add_argument("--write-traffic", metavar="DIR",
+                    help="rewrite profiles/dfa_fwd_hbm_traffic.txt from the counter runs under DIR and exit (no GPU needed)")
     ap.add_argument("--workload", default=WORKLOAD, help="name in synth.CONFIGS (default: throughput)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true",
@@ -256,11 +327,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
-    other_report = args.stages or args.stack or args.sweep or args.tile_cost or args.backward or args.copy_calibration
-    if args.steps is None:
-        args.steps = 200 if other_report or args.workload != WORKLOAD else 2000
-    if args.warmup is None:
-        args.warmup = 20 if other_report or args.workload != WORKLOAD else 50
+    if args.write_traffic:
+        write_traffic(args.write_traffic)
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs: "
                  "(b, h) units are independent, so N GPUs would each run this same kernel on B/N images). "
@@ -332,6 +401,8 @@ def main():
         if args.zero_inputs:
             g.zero_()
         steps = max(1, args.steps if cfg["dtype"] == "bf16" else min(args.steps, 20))   # the fp32 path takes tens of ms
+        if cfg["dtype"] == "bf16" and args.settle_ms > 0:
+            settle(torch, lambda: binding.backward(q, k, v, out, lse, g, branches, scale), args.settle_ms)
         for _ in range(max(1, min(args.warmup, steps))):
             binding.backward(q, k, v, out, lse, g, branches, scale)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -358,23 +429,42 @@ def main():
                                                "each kernel; useful = 5 products"}}))
         return
 
+    # a launch with few workgroups is split over several workgroups per tile: the caller's workspace for the partial results
+    need = binding.workspace_bytes(Bsz, H, N, D, binding.DFA_BF16 if cfg["dtype"] == "bf16" else binding.DFA_F32, branches)
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda") if need else None
+
+    def step():
+        binding.forward(q, k, v, branches, scale, out=out, lse=lse, workspace=ws)
+
+    # untimed: the settle phase (steady clocks), then the warm-up steps as asked for; then exactly `steps` timed steps
+    n_settle = settle(torch, step, args.settle_ms) if args.settle_ms > 0 else 0
     for _ in range(args.warmup):
-        binding.forward(q, k, v, branches, scale, out=out, lse=lse)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        binding.forward(q, k, v, branches, scale, out=out, lse=lse)
+        step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
     tflops = flops / (wall / args.steps) / 1e12
 
-    # dominant (only) kernel: mean launch duration from HIP events on the launch stream
-    kern_ms = binding.forward_timed(q, k, v, branches, scale, args.steps, out=out, lse=lse)
+    # dominant (only) kernel: mean launch duration from HIP events on the launch stream over `steps` launches, in the
+    # same steady state (the calls above are still draining when these are enqueued: no idle gap in between)
+    for _ in range(args.warmup):
+        step()
+    kern_ms = binding.forward_timed(q, k, v, branches, scale, args.steps, out=out, lse=lse, workspace=ws)
     achieved = flops / (kern_ms * 1e-3) / 1e12
-    # and the median of 50 launches timed one by one
-    singles = sorted(binding.forward_timed(q, k, v, branches, scale, 1, out=out, lse=lse) for _ in range(50))
-    kern_ms_median = 0.5 * (singles[24] + singles[25])
+    # and launch by launch: events between consecutive launches of one uninterrupted run on that same stream (torch's
+    # current stream is the stream the binding launches on); the median of the last 100 of 150
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(151)]
+    for i in range(150):
+        evs[i].record()
+        step()
+    evs[150].record()
+    torch.cuda.synchronize()
+    each = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(50, 150))
+    kern_ms_median = 0.5 * (each[49] + each[50])
 
     # the matrix cores on their own, measured now on this machine: constant and random operands
     peak_const, mhz_const = binding.mfma_peak(False)
@@ -413,6 +503,8 @@ def main():
         # kept (query, key) pair), the other two parts are pct_of_mfma_peak and encoder_attention_stack below
         "metric": "dilated-attention TFLOP/s + % MFMA peak; \u00b5s per 1024\u00b2 image (all layers)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle": {"untimed_launches_before_warmup": n_settle, "ms_asked": args.settle_ms,
+                   "why": "steady-state figure: a burst of launches starts with a clock transient of some 30 ms"},
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
         "data": "zeros (power diagnostic, not the benchmark)" if args.zero_inputs else "synthetic",
@@ -428,15 +520,17 @@ def main():
         "max_abs_err_vs_oracle": max_err,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(args.workload),
+                     "traffic": None if args.zero_inputs else read_traffic(args.workload),
                      "algorithmic_bytes": Bsz * N * H * (4 * D * (2 if cfg["dtype"] == "bf16" else 4) + 4),
                      "kernel": "dfa_fwd_bf16_kernel" if cfg["dtype"] == "bf16" else "dfa_fwd_f32_kernel",
-                     "kernel_ms": kern_ms, "kernel_ms_median_of_50": kern_ms_median,
+                     "kernel_ms": kern_ms, "kernel_ms_median_of_100": kern_ms_median,
                      "executed_flops_per_step": executed_flops,
                      "executed_TFLOP/s": executed_flops / (kern_ms * 1e-3) / 1e12,
-                     "note": "achieved counts the algorithm's flops (4*D per kept (query, key) pair of every branch); the "
-                             "kernel visits a key that several branches of a row keep once, weighted by its multiplicity, "
-                             "so it executes fewer: executed_* count those"},
+                     "mfma_utilisation_executed": executed_flops / (kern_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "note": "achieved and frac count the algorithm's flops (4*D per kept (query, key) pair of every branch) "
+                             "per launch; the kernel visits a key that several branches of a row keep once, weighted by its "
+                             "multiplicity, so the matrix cores execute fewer: executed_* and mfma_utilisation_executed "
+                             "count those (the figure to read as how busy the matrix cores are)"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -332,7 +332,7 @@ int dfa_oracle_forward_rows(const double *q, const double *k, const double *v,
 /*
  * Gradients of the operator with respect to q, k and v for a given gradient dout of its
  * output (lse takes no gradient).  The paper states no backward pass (it distils through
- * the FlashAttention library, section 4.4); this is the chain rule applied to Eq. 2 and the
+ * the FlashAttention library, section 4.3); this is the chain rule applied to Eq. 2 and the
  * branch merge.  The merged operator is a softmax over the multiset union of a row's key
  * sets:  out_n = sum over branches x and keys j of part_x(n) of P_x(n,j) v_j  with
  * P_x(n,j) = exp(scale q_n.k_j - lse_n), lse_n the merged log-sum-exp.  With

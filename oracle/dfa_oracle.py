@@ -176,7 +176,7 @@ def backward(q, k, v, dout, branches, scale, head_offsets=None):
 # The steps either side of the operator inside one encoder layer (the "encoder attention
 # stack" workload: QKV projection 768 -> 2304, dilated attention, output projection 768 -> 768;
 # no bias, residual or normalisation).  The paper names these projections only as part of the
-# ViT encoder's self-attention blocks (section 3.1 / 4.4); the feature order of the fused QKV
+# ViT encoder's self-attention blocks (section 3.1); the feature order of the fused QKV
 # output is this build's reading: feature f = t*E + h*D + d with t = 0, 1, 2 for q, k, v.
 
 def linear(x, w):
