@@ -159,9 +159,10 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
 
 def sweep_report(binding, synth, torch, np, steps, warmup):
     """Section 4.3's ablation (Fig. 4) as a synthetic sweep: image sizes 256^2, 512^2, 1024^2 (N = 256, 1024, 4096
-    tokens of 16 x 16 patches), embed 384 (6 heads) and 768 (12 heads), B = 16.  For each shape the three
-    dilated branches scaled to it ((N/4, 1), (N/2, 2), (N, 4)) against dense attention over all N tokens,
-    both through dfa_forward (dense = one branch with w = N, r = 1)."""
+    tokens of 16 x 16 patches), embed 384 (6 heads) and 768 (12 heads), B = 16.  For each shape: the three
+    dilated branches scaled to it ((N/4, 1), (N/2, 2), (N, 4)) through dfa_forward; dense attention over all N
+    tokens through dfa_forward (one branch with w = N, r = 1: "FlashAttention on"); and dense attention with the
+    score matrix held in memory (dfa_dense_unfused: "FlashAttention off")."""
     rows = []
     Bsz, D, scale = 16, 64, 0.125
     for H in (6, 12):
@@ -173,14 +174,34 @@ def sweep_report(binding, synth, torch, np, steps, warmup):
             dil = [(N // 4, 1), (N // 2, 2), (N, 4)]
             res = {"image": f"{int(N ** 0.5) * 16}^2", "N": N, "H": H, "B": Bsz}
             for name, br in (("dilated", dil), ("dense", [(N, 1)])):
-                settle(torch, lambda: binding.forward(q, k, v, br, scale, out=out, lse=lse), 60.0)
-                ms = binding.forward_timed(q, k, v, br, scale, max(steps // 4, 10), out=out, lse=lse)
+                need = binding.workspace_bytes(Bsz, H, N, D, binding.DFA_BF16, br)
+                ws = torch.empty((need,), dtype=torch.uint8, device="cuda") if need else None
+                settle(torch, lambda: binding.forward(q, k, v, br, scale, out=out, lse=lse, workspace=ws), 60.0)
+                ms = binding.forward_timed(q, k, v, br, scale, max(steps // 4, 10), out=out, lse=lse, workspace=ws)
                 fl = synth.useful_flops(Bsz, H, N, D, br)
                 res[name] = {"us": ms * 1e3, "useful_TFLOP/s": fl / ms / 1e9, "flops": fl}
+            # dense attention with the scores in memory: four launches per call
+            dws = torch.empty((binding.lib().dfa_dense_unfused_workspace_bytes(Bsz, H, N, D),), dtype=torch.uint8, device="cuda")
+            run = lambda: binding.dense_unfused(q, k, v, scale, out=out, lse=lse, workspace=dws)
+            settle(torch, run, 60.0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            it = max(steps // 4, 10)
+            e0.record()
+            for _ in range(it):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / it
+            fl = synth.useful_flops(Bsz, H, N, D, [(N, 1)])
+            res["dense_unfused"] = {"us": ms * 1e3, "useful_TFLOP/s": fl / ms / 1e9, "flops": fl,
+                                    "score_matrix_bytes": Bsz * H * N * N * 2}
             res["dense_over_dilated_time"] = res["dense"]["us"] / res["dilated"]["us"]
+            res["unfused_over_fused_dense_time"] = res["dense_unfused"]["us"] / res["dense"]["us"]
             rows.append(res)
+            del dws
     return {"sweep": rows, "note": "useful FLOPs = 4*D per (query, key) pair the method computes; dense attention "
-                                    "computes N^2 pairs per head, the three branches 7*N^2/16"}
+                                    "computes N^2 pairs per head, the three branches 7*N^2/16; dense_unfused = scores "
+                                    "materialised in memory as bf16 (QK^T product, row softmax, PV product)"}
 
 
 def tile_cost_report(binding, synth, torch, np):

@@ -25,6 +25,23 @@ int dfa_forward_timed(const void *q, const void *k, const void *v,
                       int32_t iters, float *ms);
 
 /*
+ * Comparison path of the input-size sweep: dense softmax attention over all N tokens (Eq. 2 with one segment,
+ * w = N, r = 1) computed the plain way, with the score matrix held in memory - the "FlashAttention off" side of
+ * the paper's ablation (section 4.3, Fig. 4).  Four launches on `stream`: S = Q K^T (batched matrix-core
+ * product), row softmax in place, a transpose of V, O = P V.
+ *   q, k, v, strides, B, H, N, D, scale   as in dfa_forward, bf16 only; N % 256 == 0 and N <= 4096
+ *   out         device bf16 [B, N, H, D];  lse device fp32 [B, H, N] or NULL
+ *   workspace   device, 16-byte aligned, dfa_dense_unfused_workspace_bytes() = room for the bf16 scores
+ *               [B, H, N, N] and V^T [B, H, D, N]; DFA_ERR_WORKSPACE when smaller
+ * Scores and probabilities are rounded to bf16 on their way through memory.
+ */
+size_t dfa_dense_unfused_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D);
+int dfa_dense_unfused(const void *q, const void *k, const void *v,
+                      dfa_strides_t sq, dfa_strides_t sk, dfa_strides_t sv,
+                      int32_t B, int32_t H, int32_t N, int32_t D, float scale,
+                      void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid (no part of the operator): what the matrix cores sustain on their own, the
  * ceiling that the kernels' MFMA rooflines are also quoted against.  Runs a loop of
  * independent v_mfma_f32_32x32x16_bf16 on the whole chip (two waves per SIMD, no memory

@@ -23,7 +23,7 @@ EXPORTS = [
     "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
     "dfa_release_plans", "dfa_linear", "dfa_encoder_stack", "dfa_backward",
 ]
-BENCH_EXPORTS = ["dfa_forward_timed", "dfa_mfma_peak"]
+BENCH_EXPORTS = ["dfa_forward_timed", "dfa_mfma_peak", "dfa_dense_unfused", "dfa_dense_unfused_workspace_bytes"]
 
 
 class Branch(ctypes.Structure):
@@ -90,10 +90,14 @@ def lib():
         L.dfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, ctypes.c_int,
                                    f32, ctypes.POINTER(Branch), i32, _i32p, vp, vp, vp, vp, vp]
         L.dfa_mfma_peak.argtypes = [i32, ctypes.POINTER(f32), ctypes.POINTER(f32)]
+        L.dfa_dense_unfused_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.dfa_dense_unfused.argtypes = [vp, vp, vp, Strides, Strides, Strides, i32, i32, i32, i32, f32, vp, vp, vp,
+                                        ctypes.c_size_t, vp]
         for name in EXPORTS + BENCH_EXPORTS:
-            if name not in ("dfa_error_string", "dfa_workspace_bytes"):
+            if name not in ("dfa_error_string", "dfa_workspace_bytes", "dfa_dense_unfused_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         L.dfa_workspace_bytes.restype = ctypes.c_size_t
+        L.dfa_dense_unfused_workspace_bytes.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -385,6 +389,29 @@ def backward(q, k, v, out, lse, dout, branches, scale, head_offsets=None):
                               vp(delta.data_ptr()), vp(dq.data_ptr()), vp(dk.data_ptr()), vp(dv.data_ptr()), _stream()),
            "dfa_backward")
     return dq, dk, dv
+
+
+def dense_unfused(q, k, v, scale, out=None, lse=None, workspace=None):
+    """Dense attention over all N tokens with the scores materialised in memory (the size sweep's comparison path)."""
+    import torch
+    for t, nm in ((q, "q"), (k, "k"), (v, "v")):
+        _gpu(t, nm)
+    B, N, H, D = q.shape
+    if q.dtype != torch.bfloat16:
+        raise DfaError(-4, "dense_unfused takes bf16 tensors")
+    if out is None:
+        out = torch.empty((B, N, H, D), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    need = int(lib().dfa_dense_unfused_workspace_bytes(B, H, N, D))
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=q.device)
+    vp = ctypes.c_void_p
+    _check(lib().dfa_dense_unfused(vp(q.data_ptr()), vp(k.data_ptr()), vp(v.data_ptr()), _strides(q), _strides(k), _strides(v),
+                                   B, H, N, D, ctypes.c_float(scale), vp(out.data_ptr()), vp(lse.data_ptr()),
+                                   vp(workspace.data_ptr()), ctypes.c_size_t(workspace.numel()), _stream()), "dfa_dense_unfused")
+    workspace.record_stream(torch.cuda.current_stream())
+    return out, lse
 
 
 def mfma_peak(random_operands=True):

@@ -9,7 +9,7 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_PKG), "include")
 LIB_PATH = os.path.join(_PKG, "libdfa.so")
 
-SOURCES = ["dfa_api.hip", "dfa_fwd_bf16.hip", "dfa_fwd_f32.hip", "dfa_bwd.hip", "dfa_bwd_bf16.hip", "dfa_linear_bf16.hip", "dfa_aux.hip", "dfa_probe.hip", "dfa_plan.cpp"]
+SOURCES = ["dfa_api.hip", "dfa_fwd_bf16.hip", "dfa_fwd_f32.hip", "dfa_bwd.hip", "dfa_bwd_bf16.hip", "dfa_linear_bf16.hip", "dfa_dense.hip", "dfa_aux.hip", "dfa_probe.hip", "dfa_plan.cpp"]
 
 
 def hipcc_command(out: str = LIB_PATH, extra=()):

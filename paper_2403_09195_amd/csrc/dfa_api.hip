@@ -676,6 +676,31 @@ int dfa_release_plans(void) {
     return DFA_OK;
 }
 
+size_t dfa_dense_unfused_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D) {
+    if (B <= 0 || H <= 0 || N <= 0 || D != DFA_HEAD_DIM) return 0;
+    return align256((size_t)B * H * N * N * 2) + align256((size_t)B * H * N * D * 2);
+}
+
+int dfa_dense_unfused(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
+                      dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, float scale,
+                      void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !out || !workspace) return DFA_ERR_NULL;
+    int rc = check_common(B, H, N, D, DFA_BF16);
+    if (rc != DFA_OK) return rc;
+    if (N % 256 || N > 4096) return DFA_ERR_SHAPE;       // whole 256-row tiles; a row of scores is held in registers
+    if (!std::isfinite(scale) || scale <= 0.f) return DFA_ERR_SHAPE;
+    if (!aligned_rows(q, sq, 2) || !aligned_rows(k, sk, 2) || !aligned_rows(v, sv, 2)) return DFA_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(out) % 16 || reinterpret_cast<uintptr_t>(workspace) % 16 ||
+        (lse && reinterpret_cast<uintptr_t>(lse) % 4)) return DFA_ERR_ALIGN;
+    if (sq.n <= 0 || sk.n <= 0 || sv.n <= 0 || sq.n >= ((int64_t)1 << 26) || sk.n >= ((int64_t)1 << 26)) return DFA_ERR_TOO_LARGE;
+    if ((int64_t)B * H > 65535) return DFA_ERR_TOO_LARGE;
+    if (workspace_bytes < dfa_dense_unfused_workspace_bytes(B, H, N, D)) return DFA_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    return launch_dense_unfused(q, k, v, sq.b, sq.n, sq.h, sk.b, sk.n, sk.h, sv.b, sv.n, sv.h, B, H, N, scale, out, lse,
+                                ws, ws + align256((size_t)B * H * N * N * 2), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? DFA_OK : DFA_ERR_LAUNCH;
+}
+
 int dfa_forward_timed(const void* q, const void* k, const void* v, dfa_strides_t sq, dfa_strides_t sk,
                       dfa_strides_t sv, int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype_t dt,
                       float scale, const dfa_branch_t* branches, int32_t nb, const int32_t* head_offsets,

@@ -86,6 +86,16 @@ hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hip
 hipError_t launch_bwd_bf16(const BwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                               int64_t ldx, int64_t ldw, int64_t ldy, const ChipShape& chip, hipStream_t st);
+// batch of products of one shape: matrix (z0, z1) starts at x + z0 * xs0 + z1 * xs1 etc.; M % 256 == 0, N % 64 == 0, K % 64 == 0
+hipError_t launch_linear_bf16_batched(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
+                                      int64_t ldx, int64_t ldw, int64_t ldy, int32_t batch_outer, int32_t batch_inner,
+                                      int64_t xs0, int64_t xs1, int64_t ws0, int64_t ws1, int64_t ys0, int64_t ys1,
+                                      hipStream_t st);
+// dense attention with the scores materialised in memory (comparison path of the size sweep)
+hipError_t launch_dense_unfused(const void* q, const void* k, const void* v, int64_t sqb, int64_t sqn, int64_t sqh,
+                                int64_t skb, int64_t skn, int64_t skh, int64_t svb, int64_t svn, int64_t svh,
+                                int32_t B, int32_t H, int32_t N, float scale, void* out, float* lse,
+                                void* scores, void* vt, hipStream_t st);
 hipError_t launch_index_map(int32_t N, int32_t H, int32_t w, int32_t r, const HeadOffsets& offs,
                             int32_t* d_idx, hipStream_t st);
 hipError_t launch_gather(const void* x, int64_t sb, int64_t sn, int64_t sh, int32_t B, int32_t H,

@@ -170,6 +170,19 @@ void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restri
     else linear_tile<128>(x, w, y, K, ldx, ldw, ldy, m0, n0 + 128 * ((local - wide_per_die) & 1), lds);
 }
 
+// A batch of independent products of one shape: workgroup (t, z) computes tile t of matrix z = z0 * batch_inner + z1,
+// whose operands start at x + z0 * xs0 + z1 * xs1 (elements), and likewise for w and y.  Plain tile order.
+template <int BN>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void linear_bf16_batched_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
+                                int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_n, int batch_inner,
+                                int64_t xs0, int64_t xs1, int64_t ws0, int64_t ws1, int64_t ys0, int64_t ys1) {
+    __shared__ __attribute__((aligned(1024))) char lds[kLinStages * (kLinBM + BN) * kLinBK * 2];
+    const int z0 = blockIdx.y / batch_inner, z1 = blockIdx.y % batch_inner;
+    const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * kLinBM, n0 = (int64_t)(blockIdx.x % tiles_n) * BN;
+    linear_tile<BN>(x + z0 * xs0 + z1 * xs1, w + z0 * ws0 + z1 * ws1, y + z0 * ys0 + z1 * ys1, K, ldx, ldw, ldy, m0, n0, lds);
+}
+
 template <int BN>
 hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                         int64_t ldx, int64_t ldw, int64_t ldy, const ChipShape& chip, hipStream_t st) {
@@ -200,6 +213,30 @@ hipError_t launch_linear_bf16(const void* x, const void* w, void* y, int64_t M, 
     }
     return wide ? launch_tiles<256>(x, w, y, M, N, K, ldx, ldw, ldy, chip, st)
                 : launch_tiles<128>(x, w, y, M, N, K, ldx, ldw, ldy, chip, st);
+}
+
+hipError_t launch_linear_bf16_batched(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
+                                      int64_t ldx, int64_t ldw, int64_t ldy, int32_t batch_outer, int32_t batch_inner,
+                                      int64_t xs0, int64_t xs1, int64_t ws0, int64_t ws1, int64_t ys0, int64_t ys1,
+                                      hipStream_t st) {
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    const uint16_t* wp = static_cast<const uint16_t*>(w);
+    uint16_t* yp = static_cast<uint16_t*>(y);
+    const dim3 block(512);
+    if (N % 256 == 0) {
+        const dim3 grid((unsigned)((M / kLinBM) * (N / 256)), (unsigned)(batch_outer * batch_inner));
+        hipLaunchKernelGGL((linear_bf16_batched_kernel<256>), grid, block, 0, st, xp, wp, yp, K, ldx, ldw, ldy, N / 256,
+                           batch_inner, xs0, xs1, ws0, ws1, ys0, ys1);
+    } else if (N % 128 == 0) {
+        const dim3 grid((unsigned)((M / kLinBM) * (N / 128)), (unsigned)(batch_outer * batch_inner));
+        hipLaunchKernelGGL((linear_bf16_batched_kernel<128>), grid, block, 0, st, xp, wp, yp, K, ldx, ldw, ldy, N / 128,
+                           batch_inner, xs0, xs1, ws0, ws1, ys0, ys1);
+    } else {
+        const dim3 grid((unsigned)((M / kLinBM) * (N / 64)), (unsigned)(batch_outer * batch_inner));
+        hipLaunchKernelGGL((linear_bf16_batched_kernel<64>), grid, block, 0, st, xp, wp, yp, K, ldx, ldw, ldy, N / 64,
+                           batch_inner, xs0, xs1, ws0, ws1, ys0, ys1);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace dfa
