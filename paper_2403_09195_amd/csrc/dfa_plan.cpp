@@ -194,7 +194,11 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
     auto lightest = [&]() {
         return (int)(std::min_element(die_cost.begin(), die_cost.end()) - die_cost.begin());
     };
-    const bool by_unit = (int64_t)B * H >= 4 * kNumXcd;
+    // whole units per die when that balances the dies to within an eighth (always with 4 units per die or more);
+    // every die then reads only its own units' K/V rows from memory
+    const int64_t units = (int64_t)B * H;
+    const bool by_unit = units >= 4 * kNumXcd ||
+                         (units >= kNumXcd && ((units + kNumXcd - 1) / kNumXcd) * kNumXcd * 8 <= units * 9);
     if (by_unit) {
         for (int32_t b = 0; b < B; ++b)
             for (int32_t h = 0; h < H; ++h) {
