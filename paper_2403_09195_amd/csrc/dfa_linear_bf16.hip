@@ -148,26 +148,177 @@ __device__ __forceinline__ void linear_tile(const uint16_t* __restrict__ x, cons
     }
 }
 
+// ---- the resident form used by the projections -------------------------------------------------------------
+// One workgroup per CU stays for the whole launch and works through its CU's tiles one after the other.  The
+// tiles of a launch all cost the same, so the fixed round-robin deal below is also the balanced one, and a
+// resident workgroup can do what a fresh one cannot: fetch the first k-step of its next tile while the last
+// k-step of the current one is computed, so that neither the first trip to memory of a tile nor the write-out of
+// the one before it leaves the CU's matrix cores idle.
+// LDS: two stages of a 256-row x tile and a (up to) 256-row w tile, at fixed places whatever the width of the
+// tile in hand, and a piece per wave for the write-out (16 rows at a time), apart from the stages because the
+// next tile's first stage is already arriving while the results leave.
+constexpr uint32_t kResXStage = kLinBM * kLinBK * 2;                 // 32 KB
+constexpr uint32_t kResWStage = 256 * kLinBK * 2;                    // 32 KB (a 128-feature tile uses half)
+constexpr uint32_t kResWBase = kLinStages * kResXStage;
+constexpr uint32_t kResOutBase = kResWBase + kLinStages * kResWStage;
+constexpr int kResOutPitch = 64 * 2 + 16;                            // a wave's 64 features of one row, padded
+constexpr uint32_t kResLdsBytes = kResOutBase + 8 * 16 * kResOutPitch;
+
+// One work item of a die's list: local index j < wide: the 256-feature tile j; beyond, the halves of the tiles
+// after them (see launch_tiles).  Returns false past the end of the die's list.
+struct ResItem {
+    int64_t m0, n0;
+    bool wide;
+};
+__device__ __forceinline__ bool res_item(int die, int j, int per_die, int wide_per_die, int tiles_m, int tiles_n, int bn,
+                                         ResItem* it) {
+    const bool whole = bn == 128 || j < wide_per_die;
+    const int in_die = whole ? j : wide_per_die + (j - wide_per_die) / 2;
+    const int t = die * per_die + in_die;
+    if (in_die >= per_die || t >= tiles_m * tiles_n) return false;
+    it->m0 = (int64_t)(t / tiles_n) * kLinBM;
+    it->n0 = (int64_t)(t % tiles_n) * bn + (whole ? 0 : 128 * ((j - wide_per_die) & 1));
+    it->wide = whole && bn == 256;
+    return true;
+}
+
+// The copies of k-step ks of the tile at (m0, n0), `bn` features wide, into stage `stage`.
+template <int BN>
+__device__ __forceinline__ void res_issue(const uint16_t* x, const uint16_t* w, int64_t ldx, int64_t ldw, int64_t m0,
+                                          int64_t n0, int ks, int stage, int wave, uint32_t x_off, uint32_t w_off,
+                                          uint32_t lds_addr) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int row = 32 * wave + 8 * u;
+        copy16_to_lds(uniform_ptr(x + (m0 + row) * ldx + (int64_t)ks * kLinBK), x_off, lds_addr + stage * kResXStage + row * 128);
+    }
+#pragma unroll
+    for (int u = 0; u < BN / 64; ++u) {
+        const int row = (BN / 8) * wave + 8 * u;
+        copy16_to_lds(uniform_ptr(w + (n0 + row) * ldw + (int64_t)ks * kLinBK), w_off, lds_addr + kResWBase + stage * kResWStage + row * 128);
+    }
+}
+
+// All k-steps and the write-out of one tile whose first k-step is already on its way into stage `stage`
+// (updated to the stage the next tile starts in).  `next`: the tile to prefetch during the last k-step, if any.
+template <int BN>
+__device__ __forceinline__ void res_tile(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                         uint16_t* __restrict__ y, int K, int64_t ldx, int64_t ldw, int64_t ldy,
+                                         const ResItem& cur, bool have_next, const ResItem& next, int& stage, char* lds) {
+    constexpr int NT = BN / 64;            // 16-feature blocks per wave
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r16 = lane & 15, g4 = lane >> 4;
+    const int r8 = lane >> 3;
+    const int chunk = (lane & 7) ^ lin_swizzle(r8);
+    const uint32_t x_off = (uint32_t)(r8 * ldx * 2 + 16 * chunk);
+    const uint32_t w_off = (uint32_t)(r8 * ldw * 2 + 16 * chunk);
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &lds[0]);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int frag = r16 * kLinBK + 8 * (g4 ^ lin_swizzle(r16));
+    const int x_rows = 128 * wm, w_rows = (BN / 4) * wn;
+
+    floatx4 acc[NT][8];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int n_k = K / kLinBK;
+    for (int ks = 0; ks < n_k; ++ks) {
+        wait_vmcnt<0>();           // this wave's share of stage ks has landed (and the stores of the tile before have left)
+        __syncthreads();           // everyone's has, and everyone is done reading the other stage
+        if (ks + 1 < n_k) {
+            res_issue<BN>(x, w, ldx, ldw, cur.m0, cur.n0, ks + 1, stage ^ 1, wave, x_off, w_off, lds_addr);
+        } else if (have_next) {    // the next tile's first k-step, under this tile's last one and its write-out
+            if (next.wide) res_issue<256>(x, w, ldx, ldw, next.m0, next.n0, 0, stage ^ 1, wave, x_off, w_off, lds_addr);
+            else res_issue<128>(x, w, ldx, ldw, next.m0, next.n0, 0, stage ^ 1, wave, x_off, w_off, lds_addr);
+        }
+        const uint16_t* xs = reinterpret_cast<const uint16_t*>(lds + stage * kResXStage) + x_rows * kLinBK;
+        const uint16_t* ws = reinterpret_cast<const uint16_t*>(lds + kResWBase + stage * kResWStage) + w_rows * kLinBK;
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            bf16x8 wf[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                wf[nt] = *reinterpret_cast<const bf16x8*>(ws + 16 * nt * kLinBK + (frag ^ (32 * kh)));
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) {
+                bf16x8 xf[4];
+#pragma unroll
+                for (int m4 = 0; m4 < 4; ++m4)
+                    xf[m4] = *reinterpret_cast<const bf16x8*>(xs + 16 * (4 * mh + m4) * kLinBK + (frag ^ (32 * kh)));
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int m4 = 0; m4 < 4; ++m4)
+                        acc[nt][4 * mh + m4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], xf[m4], acc[nt][4 * mh + m4], 0, 0, 0);
+            }
+        }
+        stage ^= 1;
+    }
+
+    // ---- write-out, 16 rows of the wave's tile at a time through the wave's own piece of LDS: lane (g4, r16) holds
+    // row 16*mt + r16, features 16*nt + 4*g4 .. +3; written 8 bytes per lane, read back 16 bytes per lane with
+    // consecutive lanes along a row, stored as whole rows of the wave's tile.  No barrier: the piece belongs to
+    // this wave alone, and LDS operations of a wave complete in order.
+    constexpr int kRowBytes = (BN / 4) * 2, kLanesPerRow = kRowBytes / 16, kRowsPerStore = 64 / kLanesPerRow;
+    char* mine = lds + kResOutBase + wave * (16 * kResOutPitch);
+    const int srow = lane / kLanesPerRow, schunk = lane % kLanesPerRow;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const floatx4& a = acc[nt][mt];
+            const bf16x4 o = {(__bf16)a[0], (__bf16)a[1], (__bf16)a[2], (__bf16)a[3]};
+            *reinterpret_cast<bf16x4*>(mine + r16 * kResOutPitch + (16 * nt + 4 * g4) * 2) = o;
+        }
+#pragma unroll
+        for (int s = 0; s < (16 + kRowsPerStore - 1) / kRowsPerStore; ++s) {
+            const int row = s * kRowsPerStore + srow;                      // row within these 16
+            if (kRowsPerStore <= 16 || row < 16) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * kResOutPitch + 16 * schunk);
+                uint16_t* dst = y + (cur.m0 + x_rows + 16 * mt + row) * ldy + cur.n0 + w_rows + 8 * schunk;
+                *reinterpret_cast<u32x4*>(dst) = v;
+            }
+        }
+    }
+}
+
 // Requires M % 256 == 0, N % BN == 0, K % 64 == 0, every row of x, w and y starting on a 16-byte boundary.
-// Workgroup i runs on die i % dies; tiles (256 x BN) are numbered band by band and dealt so that one die walks all
-// feature tiles of a row band before moving on (the x band is then read from memory once per die, w stays
-// in its L2).  One workgroup fits a CU at a time, so a die works its share off in rounds of one tile per CU; when
-// the last round of a die would be at most half full (wide tiles only), its tiles are cut into two
-// 128-feature halves, which fill the die for a round half as long: the first `wide_per_die` workgroups of a
-// die take whole tiles, the others halves.
+// Workgroup i stays on CU (i / dies) of die i % dies; tiles (256 x BN) are numbered band by band and dealt so that one
+// die walks all feature tiles of a row band before moving on (the x band is then read from memory once per die, w stays
+// in its L2), the CUs of a die taking them round-robin.  When the last round of a die would be at most half full
+// (wide tiles only), its tiles are cut into two 128-feature halves, which fill the die for a round half as long: the
+// first `wide_per_die` items of a die are whole tiles, the others halves.
 template <int BN>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void linear_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, uint16_t* __restrict__ y,
-                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n, int wide_per_die, int dies) {
-    __shared__ __attribute__((aligned(1024))) char lds[kLinStages * (kLinBM + BN) * kLinBK * 2];
-    const int die = blockIdx.x % dies, local = blockIdx.x / dies;
+                        int K, int64_t ldx, int64_t ldw, int64_t ldy, int tiles_m, int tiles_n, int wide_per_die, int dies,
+                        int cus_per_die) {
+    __shared__ __attribute__((aligned(1024))) char lds[kResLdsBytes];
+    const int die = blockIdx.x % dies, cu = blockIdx.x / dies;
     const int per_die = (tiles_m * tiles_n + dies - 1) / dies;
-    const bool whole = BN == 128 || local < wide_per_die;
-    const int t = die * per_die + (whole ? local : wide_per_die + (local - wide_per_die) / 2);
-    if (t >= tiles_m * tiles_n || (!whole && wide_per_die + (local - wide_per_die) / 2 >= per_die)) return;
-    const int64_t m0 = (int64_t)(t / tiles_n) * kLinBM, n0 = (int64_t)(t % tiles_n) * BN;
-    if (whole) linear_tile<BN>(x, w, y, K, ldx, ldw, ldy, m0, n0, lds);
-    else linear_tile<128>(x, w, y, K, ldx, ldw, ldy, m0, n0 + 128 * ((local - wide_per_die) & 1), lds);
+    ResItem cur, next;
+    int j = cu;
+    if (!res_item(die, j, per_die, wide_per_die, tiles_m, tiles_n, BN, &cur)) return;
+    // the first tile's first k-step
+    {
+        const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63, r8 = lane >> 3;
+        const int chunk = (lane & 7) ^ lin_swizzle(r8);
+        const uint32_t x_off = (uint32_t)(r8 * ldx * 2 + 16 * chunk), w_off = (uint32_t)(r8 * ldw * 2 + 16 * chunk);
+        const uint32_t lds_addr = (uint32_t)(uintptr_t)DFA_LDS_PTR(void, &lds[0]);
+        if (cur.wide) res_issue<256>(x, w, ldx, ldw, cur.m0, cur.n0, 0, 0, wave, x_off, w_off, lds_addr);
+        else res_issue<128>(x, w, ldx, ldw, cur.m0, cur.n0, 0, 0, wave, x_off, w_off, lds_addr);
+    }
+    int stage = 0;
+    for (;;) {                     // ends: j grows by cus_per_die >= 1 every trip, res_item fails past the die's list
+        j += cus_per_die;
+        const bool have_next = res_item(die, j, per_die, wide_per_die, tiles_m, tiles_n, BN, &next);
+        if (cur.wide) res_tile<256>(x, w, y, K, ldx, ldw, ldy, cur, have_next, next, stage, lds);
+        else res_tile<128>(x, w, y, K, ldx, ldw, ldy, cur, have_next, next, stage, lds);
+        if (!have_next) break;
+        cur = next;
+    }
 }
 
 // A batch of independent products of one shape: workgroup (t, z) computes tile t of matrix z = z0 * batch_inner + z1,
@@ -192,10 +343,11 @@ hipError_t launch_tiles(const void* x, const void* w, void* y, int64_t M, int32_
     // wide tiles: whole rounds of a die's CUs as they are, a last round that is at most half full in halves
     const int rem = per_die % cus_per_die;
     const int wide_per_die = (BN == 256 && rem > 0 && 2 * rem <= cus_per_die) ? per_die - rem : per_die;
-    const int wg_per_die = wide_per_die + 2 * (per_die - wide_per_die);
+    const int items_per_die = wide_per_die + 2 * (per_die - wide_per_die);
+    const int wg_per_die = items_per_die < cus_per_die ? items_per_die : cus_per_die;      // one resident workgroup per CU
     hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3(wg_per_die * dies), dim3(512), 0, st,
                        static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(y),
-                       K, ldx, ldw, ldy, tiles_m, tiles_n, wide_per_die, dies);
+                       K, ldx, ldw, ldy, tiles_m, tiles_n, wide_per_die, dies, cus_per_die);
     return hipGetLastError();
 }
 
