@@ -53,15 +53,17 @@ def randn(rng, *shape):
     return rng.standard_normal(shape)
 
 
-def multiset_attention_backward(q, k, v, dout, scale, branches, head_offsets=None):
+def multiset_attention_backward(q, k, v, dout, scale, branches, head_offsets=None, want_sq=False):
     """Chain rule on the multiset softmax, written with dense matrices per (b, h):
       P = mult * exp(scale q k^T - lse),  out = P v,  delta = rowsum(dout * out),  dP = dout v^T,
       dS = P * (dP - delta),  dq = scale dS k,  dk = scale dS^T q,  dv = P^T dout.
     Returns (dq, dk, dv, dq_abs, dk_abs, dv_abs), all [B, N, H, D] fp64.  The *_abs arrays are the same sums
     over absolute values of their terms, with |dP - delta| bounded by |dP| + rowsum(|dout * out|): what a
-    rounding error of relative size eps in every term can at most add up to is eps times them."""
+    rounding error of relative size eps in every term can at most add up to is eps times them.
+    want_sq: three more arrays, the root of the sum of the squared terms of every element (what independent
+    rounding errors of the terms add up to, in standard deviations per unit of their own)."""
     B, N, H, D = q.shape
-    res = [np.zeros((B, N, H, D)) for _ in range(6)]
+    res = [np.zeros((B, N, H, D)) for _ in range(9 if want_sq else 6)]
     for h in range(H):
         mult = multiplicity_matrix(N, h, branches, head_offsets).astype(np.float64)
         has = mult.sum(axis=1) > 0
@@ -84,4 +86,8 @@ def multiset_attention_backward(q, k, v, dout, scale, branches, head_offsets=Non
             res[3][b, :, h] = scale * (W @ np.abs(kh))
             res[4][b, :, h] = scale * (W.T @ np.abs(qh))
             res[5][b, :, h] = P.T @ np.abs(gh)
+            if want_sq:
+                res[6][b, :, h] = scale * np.sqrt((dS ** 2) @ (kh ** 2))
+                res[7][b, :, h] = scale * np.sqrt((dS ** 2).T @ (qh ** 2))
+                res[8][b, :, h] = np.sqrt((P ** 2).T @ (gh ** 2))
     return tuple(res)
