@@ -121,6 +121,51 @@ def test_stage_entry_points_reject_bad_arguments_before_any_gpu_work(B):
     assert merge(N=1 << 22, H=64) == -7                      # one image no longer fits 32-bit counters
 
 
+def test_stack_static_and_dense_entry_points_reject_bad_arguments_before_any_gpu_work(B):
+    """dfa_encoder_stack checks every argument before its first launch (so an error never leaves a workspace half
+    written); dfa_forward_static and dfa_dense_unfused likewise.  Fake, aligned pointers: every case here is refused."""
+    L, vp, fake = B.lib(), ctypes.c_void_p, 0x10000
+
+    def stack(layers=2, Bsz=1, H=2, N=256, D=64, scale=0.125, branches=((64, 1),), offs=None, x=fake, ws=None, ws_bytes=0, nb=None):
+        br, n = B._branches(list(branches))
+        return L.dfa_encoder_stack(vp(x), vp(fake), vp(fake), layers, Bsz, H, N, D, ctypes.c_float(scale), br,
+                                   n if nb is None else nb, B._i32_array(offs), vp(fake), vp(fake), vp(fake), vp(ws),
+                                   ctypes.c_size_t(ws_bytes), None)
+
+    assert stack(x=None) == -1
+    assert stack(layers=0) == -2 and stack(D=32) == -2
+    assert stack(N=200) == -2                                  # B * N is no multiple of the 256-row tile
+    assert stack(H=3) == -2                                    # embed 192 is no multiple of 128
+    assert stack(branches=((64, 0),)) == -2                    # r < 1: found before the first projection is enqueued
+    assert stack(offs=[[0, 1]]) == -2                          # offset outside [0, r)
+    assert stack(scale=-1.0) == -2 and stack(scale=float("inf")) == -2
+    assert stack(nb=0) == -3
+    assert stack(x=0x10004) == -5 and stack(ws=0x20008, ws_bytes=1 << 20) == -5
+
+    st = B.Strides(64 * 2 * 64, 2 * 64, 64)
+    br, nb = B._branches([(16, 2)])
+
+    def static(q=fake, out=fake, D=64, dt=0, scale=0.125, nbr=nb):
+        return L.dfa_forward_static(vp(q), vp(fake), vp(fake), st, st, st, 1, 2, 64, D, dt, ctypes.c_float(scale), br, nbr,
+                                    None, vp(out), vp(fake), None)
+
+    assert static(q=None) == -1 and static(out=None) == -1
+    assert static(D=128) == -2 and static(scale=0.0) == -2 and static(nbr=9) == -3 and static(dt=4) == -4
+    assert static(q=0x10002) == -5
+
+    def dense(q=fake, N=256, D=64, scale=0.125, ws=fake, ws_bytes=1 << 30, Bsz=1, H=2):
+        s2 = B.Strides(N * H * 64, H * 64, 64)
+        return L.dfa_dense_unfused(vp(q), vp(fake), vp(fake), s2, s2, s2, Bsz, H, N, D, ctypes.c_float(scale), vp(fake),
+                                   vp(fake), vp(ws), ctypes.c_size_t(ws_bytes), None)
+
+    assert dense(q=None) == -1 and dense(ws=None) == -1
+    assert dense(N=200) == -2 and dense(N=8192) == -2 and dense(D=32) == -2 and dense(scale=0.0) == -2
+    assert dense(q=0x10008) == -5
+    assert dense(ws_bytes=1024) == B.DFA_ERR_WORKSPACE
+    assert L.dfa_dense_unfused_workspace_bytes(2, 3, 256, 64) == 2 * 3 * 256 * 256 * 2 + 2 * 3 * 256 * 64 * 2
+    assert L.dfa_dense_unfused_workspace_bytes(2, 3, 256, 32) == 0
+
+
 def _expected_multiset(N, h, n, branches, offs):
     """(how often each token is a key of row n, the plain list of (first key, stride, count, 1)), from the
     definition: one visit per branch that keeps both n and the key in the same part."""
