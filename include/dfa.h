@@ -42,8 +42,8 @@
  *     empties the cache.  Calls may come from several threads and on several streams at once:
  *     a plan is shared and never written after its upload.
  *   - Workspace.  A bf16 dfa_forward with fewer workgroups than the chip has room for (a single
- *     image, say) is faster when every tile is walked by several workgroups whose fp32 partial
- *     results are merged afterwards.  Those partial results live in a workspace that the caller
+ *     image, say) is faster when the long key walks are shared out over several workgroups
+ *     whose fp32 partial results are merged afterwards.  Those partial results live in a workspace that the caller
  *     owns: dfa_workspace_bytes() says how much the shape needs (0 = none), and each call that
  *     may overlap another one needs a workspace of its own.  With workspace == NULL the call
  *     runs unsplit: same results to within rounding, slower for such shapes.

@@ -37,9 +37,11 @@ struct DevicePlan {
     int32_t n_items = 0;
     int device = 0;
     size_t bytes = 0;
-    // launches with few workgroups walk every tile with `split` workgroups (see launch_fwd_bf16_split)
-    // when the caller brings a workspace for their fp32 partial results
-    int32_t split = 1;
+    // launches with few workgroups walk their tiles with n_split_wgs workgroups in all (see split_plan and
+    // launch_fwd_bf16_split) when the caller brings a workspace for their fp32 partial results; 0: never split
+    const SplitWg* split_wgs = nullptr;
+    const ItemParts* item_parts = nullptr;
+    int32_t n_split_wgs = 0;
     bool owned = true;          // base came from hipMalloc and is freed with the plan
 
     DevicePlan() = default;
@@ -60,12 +62,13 @@ struct DevicePlan {
 using PlanRef = std::shared_ptr<const DevicePlan>;
 
 // The host plan laid out as the kernels read it: rows, then key progressions (plus one spare entry: a tile
-// without progressions still reads inside the array), then launch items, each part 256-byte aligned.
+// without progressions still reads inside the array), then launch items, then the workgroups and the per-item
+// shares of a split launch, each part 256-byte aligned.
 struct PackedPlan {
     std::vector<char> bytes;
-    size_t off_segs = 0, off_items = 0;
+    size_t off_segs = 0, off_items = 0, off_split_wgs = 0, off_item_parts = 0;
     int32_t n_items = 0;
-    int32_t split = 1;
+    int32_t n_split_wgs = 0;
 };
 
 constexpr int kPlanOrder = 3;              // launch order of build_plan (see dfa_plan.cpp)
@@ -74,9 +77,9 @@ constexpr size_t kMaxCachedBytes = (size_t)256 << 20;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// fp32 partial results of a split launch: out [split][B, N, H, D], then lse [split][B, H, N]
-size_t split_bytes(int32_t split, int64_t rows_total) {
-    return split >= 2 ? align256((size_t)split * rows_total * (DFA_HEAD_DIM + 1) * sizeof(float)) : 0;
+// fp32 partial results of a split launch: one block (a tile's rows of out, then of lse) per workgroup
+size_t split_bytes(int32_t n_split_wgs) {
+    return n_split_wgs > 0 ? align256((size_t)n_split_wgs * kSplitBlockFloats * sizeof(float)) : 0;
 }
 
 int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets,
@@ -87,14 +90,23 @@ int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t n
     const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
     const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
     const size_t b_items = align256(hp.items.size() * sizeof(Item));
-    out->bytes.assign(b_rows + b_segs + b_items, 0);
+    split_plan(&hp, chip);
+    const size_t b_wgs = align256(hp.split_wgs.size() * sizeof(SplitWg));
+    const size_t b_parts = align256(hp.item_parts.size() * sizeof(ItemParts));
+    out->bytes.assign(b_rows + b_segs + b_items + b_wgs + b_parts, 0);
     out->off_segs = b_rows;
     out->off_items = b_rows + b_segs;
+    out->off_split_wgs = out->off_items + b_items;
+    out->off_item_parts = out->off_split_wgs + b_wgs;
     if (!hp.rows.empty()) std::memcpy(out->bytes.data(), hp.rows.data(), hp.rows.size() * sizeof(int32_t));
     if (!hp.segs.empty()) std::memcpy(out->bytes.data() + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg));
     if (!hp.items.empty()) std::memcpy(out->bytes.data() + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item));
+    if (!hp.split_wgs.empty()) {
+        std::memcpy(out->bytes.data() + out->off_split_wgs, hp.split_wgs.data(), hp.split_wgs.size() * sizeof(SplitWg));
+        std::memcpy(out->bytes.data() + out->off_item_parts, hp.item_parts.data(), hp.item_parts.size() * sizeof(ItemParts));
+    }
     out->n_items = (int32_t)hp.items.size();
-    out->split = split_factor(hp, chip);
+    out->n_split_wgs = (int32_t)hp.split_wgs.size();
     return DFA_OK;
 }
 
@@ -107,7 +119,9 @@ void point_plan(DevicePlan* dp, void* base, const PackedPlan& pp, int device) {
     dp->n_items = pp.n_items;
     dp->device = device;
     dp->bytes = pp.bytes.size();
-    dp->split = pp.split;
+    dp->split_wgs = reinterpret_cast<const SplitWg*>(b + pp.off_split_wgs);
+    dp->item_parts = reinterpret_cast<const ItemParts*>(b + pp.off_item_parts);
+    dp->n_split_wgs = pp.n_split_wgs;
 }
 
 std::vector<int32_t> plan_key(int device, int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
@@ -295,18 +309,13 @@ int launch_forward(const DevicePlan& dp, const void* q, const void* k, const voi
     p.out = out; p.lse = lse;
     p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
     p.H = H; p.N = N; p.scale = scale;
-    p.split = 1; p.part_rows = 0;
+    p.split_wgs = dp.split_wgs; p.item_parts = dp.item_parts; p.split_ws = split_ws;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (dt == DFA_BF16 && !out_f32 && dp.split >= 2 && split_ws) {
+    if (dt == DFA_BF16 && !out_f32 && dp.n_split_wgs > 0 && split_ws) {
         // few workgroups: partial results per share of the key walk, then their log-sum-exp merge
-        const int64_t rows_total = (int64_t)B * N * H;
-        float* part_out = split_ws;
-        float* part_lse = split_ws + (size_t)dp.split * rows_total * DFA_HEAD_DIM;
-        p.out = part_out; p.lse = part_lse;
-        p.split = dp.split; p.part_rows = rows_total;
-        e = launch_fwd_bf16_split(p, dp.n_items, st);
-        if (e == hipSuccess) e = launch_merge(part_out, part_lse, dp.split, B, H, N, true, out, lse, st);
+        e = launch_fwd_bf16_split(p, dp.n_split_wgs, st);
+        if (e == hipSuccess) e = launch_merge_split(p, dp.n_items, st);
     } else if (dt == DFA_BF16) {
         e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
     } else {
@@ -326,8 +335,8 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
     if (rc != DFA_OK) return rc;
     float* split_ws = nullptr;
-    if (workspace && dt == DFA_BF16 && !out_f32 && dp->split >= 2) {
-        if (workspace_bytes < split_bytes(dp->split, (int64_t)B * N * H)) return DFA_ERR_WORKSPACE;
+    if (workspace && dt == DFA_BF16 && !out_f32 && dp->n_split_wgs > 0) {
+        if (workspace_bytes < split_bytes(dp->n_split_wgs)) return DFA_ERR_WORKSPACE;
         split_ws = static_cast<float*>(workspace);
     }
     return launch_forward(*dp, q, k, v, sq, sk, sv, B, H, N, dt, scale, out, out_f32, lse, split_ws, stream);
@@ -420,7 +429,7 @@ int dfa_forward_static(const void* q, const void* k, const void* v, dfa_strides_
             rc = pack_plan(B, H, N, branches, nb, head_offsets, chip, &pp);
             if (rc != DFA_OK) return rc;
             const size_t plan_bytes = align256(pp.bytes.size());
-            const size_t part_bytes = dt == DFA_BF16 ? split_bytes(pp.split, (int64_t)B * N * H) : 0;
+            const size_t part_bytes = dt == DFA_BF16 ? split_bytes(pp.n_split_wgs) : 0;
             if (plan_bytes + part_bytes > kStaticScratchBytes) return DFA_ERR_WORKSPACE;
             // launches of earlier calls may still be reading the plan that is about to be overwritten
             ss.holds_plan = false;
@@ -433,12 +442,12 @@ int dfa_forward_static(const void* q, const void* k, const void* v, dfa_strides_
             ss.plan_bytes = plan_bytes;
             ss.key = std::move(key);
             ss.holds_plan = true;
-        } else if (dt == DFA_BF16 && ss.plan_bytes + split_bytes(ss.plan.split, (int64_t)B * N * H) > kStaticScratchBytes) {
+        } else if (dt == DFA_BF16 && ss.plan_bytes + split_bytes(ss.plan.n_split_wgs) > kStaticScratchBytes) {
             return DFA_ERR_WORKSPACE;      // the plan was left by a call in the other precision, which needs no partial results
         }
         // the partial results of a split launch are written in full by that launch before its merge reads them:
         // nothing in the scratch has to start at zero
-        float* split_ws = ss.plan.split >= 2 ? reinterpret_cast<float*>(ss.ptr + ss.plan_bytes) : nullptr;
+        float* split_ws = ss.plan.n_split_wgs > 0 ? reinterpret_cast<float*>(ss.ptr + ss.plan_bytes) : nullptr;
         return launch_forward(ss.plan, q, k, v, sq, sk, sv, B, H, N, dt, scale, out, dt == DFA_F32, lse, split_ws, stream);
     } catch (const std::bad_alloc&) {
         return DFA_ERR_LAUNCH;
@@ -591,14 +600,14 @@ int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t
         PlanRef dp;
         rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
         if (rc != DFA_OK) return rc;
-        if (workspace && dp->split >= 2 && workspace_bytes < split_bytes(dp->split, (int64_t)B * N * H))
+        if (workspace && dp->n_split_wgs > 0 && workspace_bytes < split_bytes(dp->n_split_wgs))
             return DFA_ERR_WORKSPACE;
         for (int l = 0; l < layers; ++l) {
             rc = dfa_linear(l == 0 ? x : y, wq + (int64_t)l * 3 * E * E, qkv_ws, M, (int32_t)(3 * E), (int32_t)E,
                             E, E, 3 * E, stream);
             if (rc != DFA_OK) return rc;
             rc = launch_forward(*dp, qkv, qkv + E, qkv + 2 * E, sq, sq, sq, B, H, N, DFA_BF16, scale, attn_ws, false,
-                                nullptr, dp->split >= 2 ? static_cast<float*>(workspace) : nullptr, stream);
+                                nullptr, dp->n_split_wgs > 0 ? static_cast<float*>(workspace) : nullptr, stream);
             if (rc != DFA_OK) return rc;
             rc = dfa_linear(attn_ws, wo + (int64_t)l * E * E, y, M, (int32_t)E, (int32_t)E, E, E, E, stream);
             if (rc != DFA_OK) return rc;
@@ -619,7 +628,8 @@ size_t dfa_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype
         if (current_chip(&device, &chip) != DFA_OK) (void)hipGetLastError();
         HostPlan hp;
         build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, chip, &hp);
-        return split_bytes(split_factor(hp, chip), (int64_t)B * N * H);
+        split_plan(&hp, chip);
+        return split_bytes((int32_t)hp.split_wgs.size());
     } catch (const std::bad_alloc&) {
         return 0;
     }

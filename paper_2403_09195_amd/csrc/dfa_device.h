@@ -30,11 +30,12 @@ struct FwdParams {
     const Item* items;
     int32_t H, N;
     float scale;        // multiplies q.k
-    // Split launches only (few workgroups, see launch_fwd_bf16_split): every tile is walked by
-    // `split` workgroups, each over its share of the tile's 64-key steps; part x writes fp32
-    // results to out + x * part_rows * D and lse + x * part_rows, merged afterwards.
-    int32_t split;
-    int64_t part_rows;  // B * N * H
+    // Split launches only (few workgroups, see launch_fwd_bf16_split): workgroup g walks the share of a tile's
+    // 64-key steps that split_wgs[g] names and leaves its fp32 partial result in block g of split_ws;
+    // launch_merge_split then writes out and lse.
+    const SplitWg* split_wgs;
+    const ItemParts* item_parts;
+    float* split_ws;
 };
 
 // Arguments of the backward kernels.  out, dout, dq, dk, dv are contiguous [B, N, H, D].
@@ -80,7 +81,8 @@ __device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o
 
 // Launchers (defined in the .hip files); every one returns the hipError_t of the launch.
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
-hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_items, hipStream_t st);
+hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, hipStream_t st);
+hipError_t launch_merge_split(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st);
 hipError_t launch_bwd_bf16(const BwdParams& p, int n_items, hipStream_t st);

@@ -278,7 +278,8 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
     l_run[1] += psum[1];
 }
 
-// kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split).
+// kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves an fp32
+// partial result (rows in tile order) in its own block of the workspace; OutT is float then.
 template <typename OutT, bool kSplit>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void dfa_fwd_bf16_kernel(const FwdParams p) {
@@ -287,8 +288,14 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     __shared__ int32_t row_idx[kTileRows];
     __shared__ KeySeg seg_lds[kMaxTileSegs];
 
-    const int part = kSplit ? (int)(blockIdx.x % (unsigned)p.split) : 0;
-    const Item item = p.items[kSplit ? blockIdx.x / (unsigned)p.split : blockIdx.x];
+    int part = 0, nparts = 1, item_index = blockIdx.x;
+    if (kSplit) {
+        const SplitWg sw = p.split_wgs[blockIdx.x];
+        item_index = sw.item;
+        part = sw.part_nparts & 0xffff;
+        nparts = sw.part_nparts >> 16;
+    }
+    const Item item = p.items[item_index];
     if (item.tile < 0) return;
     const Tile tile = item.t;
     const int tid = threadIdx.x;
@@ -321,10 +328,16 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     if (tid < tile.nseg) seg_lds[tid] = my_seg;
     __syncthreads();
 
-    OutT* const out = static_cast<OutT*>(p.out) + (kSplit ? part * p.part_rows * kD : 0);
-    float* const lse_out = kSplit ? p.lse + part * p.part_rows : p.lse;
+    OutT* const out = static_cast<OutT*>(p.out);
+    float* const lse_out = p.lse;
     const int64_t out_bh = (int64_t)b * p.N * p.H + h;   // in rows; row n adds n * H
+    // split launches: this workgroup's block of partial results, out [256][64] then lse [256], rows in tile order
+    float* const blk = kSplit ? p.split_ws + (int64_t)blockIdx.x * kSplitBlockFloats : nullptr;
 
+    if (kSplit && tile.nseg == 0) {
+        blk[kTileRows * kD + tid] = -INFINITY;     // the merge writes the zero rows
+        return;
+    }
     if (tile.nseg == 0) {
         // rows that no branch keeps: the zero matrix of Eq. 3 shows through, lse = -inf
         constexpr int kChunks = kD * sizeof(OutT) / 16;
@@ -380,10 +393,10 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     pf.t = 0;
     if (kSplit) {
         // this workgroup's share of the steps: [first, last) of the tile's n_steps
-        const int first = part * n_steps / p.split, last = (part + 1) * n_steps / p.split;
+        const int first = part * n_steps / nparts, last = (part + 1) * n_steps / nparts;
         n_steps = last - first;
         if (n_steps == 0) {        // a tile with fewer steps than parts: this part has no keys
-            if (tid < tile.nrows) lse_out[((int64_t)b * p.H + h) * p.N + row_idx[tid]] = -INFINITY;
+            blk[kTileRows * kD + tid] = -INFINITY;
             return;
         }
         int skip = first;
@@ -529,8 +542,12 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const int slot = wave * 64 + qb * 32 + j_e;
         const float l_tot = l_run[qb];
         inv[qb] = 1.0f / l_tot;
-        if (lse_out && g_e == 0 && slot < tile.nrows)
-            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        const float lse_row = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        if (kSplit) {
+            if (g_e == 0) blk[kTileRows * kD + slot] = slot < tile.nrows ? lse_row : -INFINITY;
+        } else if (lse_out && g_e == 0 && slot < tile.nrows) {
+            lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = lse_row;
+        }
     }
     if constexpr (sizeof(OutT) == 2) {
         // bf16 rows are 128 bytes.  A lane holds 4 consecutive d of one row per register quad; written
@@ -569,7 +586,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             const int slot = wave * 64 + qb * 32 + j_e;
             if (slot < tile.nrows) {
                 const int64_t n = row_idx[slot];
-                OutT* op = out + (out_bh + n * p.H) * kD;
+                OutT* op = kSplit ? reinterpret_cast<OutT*>(blk) + slot * kD : out + (out_bh + n * p.H) * kD;
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -582,6 +599,59 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     }
 }
 
+// Merge of a split launch: combines the partial results of a launch item's shares by their log-sum-exp weights (the
+// same formula as the stand-alone branch merge: a share is attention over a part of the row's keys) and writes the
+// rows at their tokens.  Grid (items, 16): a workgroup takes sixteen rows of the tile, sixteen lanes to a row with
+// four features each; all loads go out before the first is used.
+__global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
+    const Item item = p.items[blockIdx.x];
+    if (item.tile < 0) return;
+    const Tile tile = item.t;
+    const int r = blockIdx.y * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
+    if (r >= tile.nrows) return;
+    const ItemParts ip = p.item_parts[blockIdx.x];
+    const float* blk0 = p.split_ws + (int64_t)ip.first_wg * kSplitBlockFloats;
+    const int32_t n = p.rows[tile.row_begin + r];
+    float lb[kMaxSplit];
+    float4 o[kMaxSplit];
+#pragma unroll
+    for (int x = 0; x < kMaxSplit; ++x) {
+        lb[x] = -INFINITY;
+        o[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (x < ip.nparts) {
+            lb[x] = blk0[(int64_t)x * kSplitBlockFloats + kTileRows * kD + r];
+            o[x] = *reinterpret_cast<const float4*>(blk0 + (int64_t)x * kSplitBlockFloats + r * kD + 4 * sub);
+        }
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int x = 0; x < kMaxSplit; ++x) m = fmaxf(m, lb[x]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float L = -INFINITY;
+    if (m > -INFINITY) {
+        float w[kMaxSplit], z = 0.f;
+#pragma unroll
+        for (int x = 0; x < kMaxSplit; ++x) {
+            w[x] = __builtin_amdgcn_exp2f((lb[x] - m) * kLog2e);      // 0 for shares without keys
+            z += w[x];
+        }
+        const float inv = 1.0f / z;
+        L = m + __builtin_amdgcn_logf(z) * kLn2;
+#pragma unroll
+        for (int x = 0; x < kMaxSplit; ++x) {
+            if (lb[x] == -INFINITY) continue;      // such a share has written no rows: its block holds anything
+            const float ws = w[x] * inv;
+            acc.x = fmaf(ws, o[x].x, acc.x);
+            acc.y = fmaf(ws, o[x].y, acc.y);
+            acc.z = fmaf(ws, o[x].z, acc.z);
+            acc.w = fmaf(ws, o[x].w, acc.w);
+        }
+    }
+    const bf16x4 ob = {(__bf16)acc.x, (__bf16)acc.y, (__bf16)acc.z, (__bf16)acc.w};
+    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.out) + (((int64_t)item.b * p.N + n) * p.H + tile.h) * kD + 4 * sub) = ob;
+    if (p.lse && sub == 0) p.lse[((int64_t)item.b * p.H + tile.h) * p.N + n] = L;
+}
+
 }  // namespace
 
 hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st) {
@@ -592,11 +662,16 @@ hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStr
     return hipGetLastError();
 }
 
-// Launches with fewer workgroups than the chip has CUs are bound by the longest tile's walk, not by
-// throughput: here every tile is walked by p.split workgroups, each over a share of its steps,
-// into fp32 partial results (p.out, p.lse: [split][...]) that the caller merges by their lse.
-hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_items, hipStream_t st) {
-    hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true>), dim3(n_items * p.split), dim3(256), 0, st, p);
+// Launches with few workgroups are bound by the longest tile's walk, not by throughput: there the tiles are walked by
+// several workgroups each (p.split_wgs), every one over a share of the steps, into fp32 partial results (p.split_ws)
+// that launch_merge_split combines.
+hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, hipStream_t st) {
+    hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge_split(const FwdParams& p, int n_items, hipStream_t st) {
+    hipLaunchKernelGGL(merge_split_kernel, dim3(n_items, kTileRows / 16), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

@@ -264,15 +264,44 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             plan->items.push_back(p < per_die[d].size() ? per_die[d][p] : Item{-1, 0, Tile{0, 0, 0, 0, 0, 0}});
 }
 
-int32_t split_factor(const HostPlan& plan, const ChipShape& chip) {
-    constexpr int kMaxSplit = 4;
-    constexpr int kMinShareSteps = 8;    // a share of fewer 64-key steps is not worth a partial result and its merge
-    const int64_t slots = chip.fwd_slots(), items = (int64_t)std::max<size_t>(plan.items.size(), 1);
-    if (items * 2 > slots) return 1;
-    int64_t longest = 0;
-    for (const Tile& t : plan.tiles) longest = std::max<int64_t>(longest, t.n_steps);
-    const int64_t split = std::min<int64_t>(std::min<int64_t>(kMaxSplit, longest / kMinShareSteps), slots / items);
-    return split >= 2 ? (int32_t)split : 1;
+void split_plan(HostPlan* plan, const ChipShape& chip) {
+    plan->split_wgs.clear();
+    plan->item_parts.clear();
+    const int64_t slots = chip.fwd_slots(), n_items = (int64_t)plan->items.size();
+    if (n_items == 0 || n_items * 2 > slots) return;
+    std::vector<int32_t> parts(n_items, 0);
+    int64_t total = 0;
+    for (int64_t i = 0; i < n_items; ++i)
+        if (plan->items[i].tile >= 0) {
+            parts[i] = 1;
+            ++total;
+        }
+    // one more share for the tile with the longest shares, as long as slots are left and the shares stay long enough
+    bool any = false;
+    while (total < slots) {
+        int64_t best = -1;
+        int32_t best_share = 0;
+        for (int64_t i = 0; i < n_items; ++i) {
+            if (parts[i] == 0 || parts[i] >= kMaxSplit) continue;
+            const int32_t steps = plan->items[i].t.n_steps;
+            if (steps / (parts[i] + 1) < kMinShareSteps) continue;
+            const int32_t share = (steps + parts[i] - 1) / parts[i];
+            if (share > best_share) {
+                best_share = share;
+                best = i;
+            }
+        }
+        if (best < 0) break;
+        ++parts[best];
+        ++total;
+        any = true;
+    }
+    if (!any) return;
+    plan->item_parts.resize(n_items);
+    for (int64_t i = 0; i < n_items; ++i) {
+        plan->item_parts[i] = ItemParts{(int32_t)plan->split_wgs.size(), parts[i]};
+        for (int32_t x = 0; x < parts[i]; ++x) plan->split_wgs.push_back(SplitWg{(int32_t)i, x | (parts[i] << 16)});
+    }
 }
 
 }  // namespace dfa

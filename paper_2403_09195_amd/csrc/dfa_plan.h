@@ -50,12 +50,29 @@ struct ChipShape {
     int32_t fwd_slots_per_die() const { return fwd_slots() / (dies > 0 ? dies : 1); }
 };
 
+// Split launches (few workgroups, see split_plan): workgroup g of the launch walks share `part` of `nparts` of the
+// 64-key steps of launch item `item` and leaves its fp32 partial result in block g of the workspace
+// (kSplitBlockFloats floats: out [256 rows][64], then lse [256], rows in tile order).
+struct SplitWg {
+    int32_t item;
+    int32_t part_nparts;    // part | nparts << 16
+};
+struct ItemParts {          // per launch item: its workgroups are first_wg .. first_wg + nparts - 1 (nparts = 0: padding)
+    int32_t first_wg;
+    int32_t nparts;
+};
+constexpr int kSplitBlockFloats = kTileRows * (DFA_HEAD_DIM + 1);
+constexpr int kMaxSplit = 4;             // most shares a tile is cut into
+constexpr int kMinShareSteps = 8;        // a share of fewer 64-key steps is not worth a partial result and its merge
+
 struct HostPlan {
     std::vector<Tile> tiles;
     std::vector<int32_t> rows;
     std::vector<KeySeg> segs;
     std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs
     std::vector<Item> items;
+    std::vector<SplitWg> split_wgs;      // empty: the launch is not split
+    std::vector<ItemParts> item_parts;
 };
 
 // Validates the branch list (DFA_OK or a negative status).  offsets: [nb][H] or nullptr.
@@ -71,9 +88,11 @@ inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
                 const int32_t* offsets, int order_mode, const ChipShape& chip, HostPlan* plan);
 
-// Launches of the bf16 forward kernel with fewer workgroups than the chip has slots walk every tile with
-// several workgroups, each over a share of its 64-key steps, into fp32 partial results that a merge launch
-// combines.  Returns the number of shares per tile (1 = no split) for a built plan.
-int32_t split_factor(const HostPlan& plan, const ChipShape& chip);
+// Launches of the bf16 forward kernel with fewer workgroups than half the chip's slots are as long as their longest
+// tile's walk.  There the walks are cut: every tile gets one workgroup, then the workgroup slots left over go one by
+// one to the tile whose shares are longest (up to kMaxSplit shares, none shorter than kMinShareSteps), and a second,
+// small launch merges the partial results by their log-sum-exp weights.  Fills plan->split_wgs / item_parts, or
+// leaves them empty when the launch is not to be split.
+void split_plan(HostPlan* plan, const ChipShape& chip);
 
 }  // namespace dfa

@@ -79,16 +79,17 @@ def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
 
 
 def test_workspace_bytes_follows_the_split_rule(B):
-    """Room for the fp32 partial results (out and lse) of every share of a split launch: the single-image
-    workload has 192 tiles for 512 workgroup slots, so two workgroups walk each tile; the batch of 16 fills
-    the chip and needs none.  (Without a device the library assumes the MI355X's 256 compute units.)"""
+    """Room for the fp32 partial results of a split launch, one block of 256 rows (out, then lse) per workgroup:
+    the single-image workload has 192 tiles of 16, 24 or 32 steps for 512 workgroup slots, and the longest walks
+    are shared out until every slot has a workgroup; the batch of 16 fills the chip and needs none.  (Without a
+    device the library assumes the MI355X's 256 compute units.)"""
     wl = [(1024, 1), (2048, 2), (4096, 4)]
-    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, wl) == 2 * 4096 * 12 * 65 * 4
+    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, wl) == 512 * 256 * 65 * 4
     assert B.workspace_bytes(16, 12, 4096, 64, B.DFA_BF16, wl) == 0
     assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_F32, wl) == 0
     assert B.workspace_bytes(1, 12, 4096, 128, B.DFA_BF16, wl) == 0          # D the library does not take
     assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, [(1024, 0)]) == 0   # r < 1
-    # walks too short to share (fewer than 16 steps of 64 keys): no split however few the tiles
+    # walks too short to share (a share would have fewer than 8 steps of 64 keys): no split however few the tiles
     assert B.workspace_bytes(1, 2, 512, 64, B.DFA_BF16, [(512, 1)]) == 0
 
 

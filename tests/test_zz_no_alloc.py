@@ -27,7 +27,7 @@ def _same(a, b):
 
 def test_static_scratch_matches_dfa_forward_on_consecutive_calls(B, oracle):
     import torch
-    # 1: a single image, the launch that is split over two workgroups per tile (plan and partial results in the scratch)
+    # 1: a single image, the launch whose key walks are split over several workgroups per tile (plan and partial results in the scratch)
     (q, k, v), ex = make_qkv(950, 1, 4096, 12, 64, "bf16")
     assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, SAM_BRANCHES) > 0
     ref1 = B.forward(q, k, v, SAM_BRANCHES, 0.125)
