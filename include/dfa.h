@@ -217,7 +217,8 @@ int dfa_scatter(const void *og, int32_t B, int32_t H, int32_t N, int32_t D, dfa_
                 dfa_branch_t br, const int32_t *head_offsets, void *out, void *stream);
 
 /*
- * Host-side view of the launch plan dfa_forward would use (no GPU needed): the query
+ * Host-side view of the launch plan of the fp32 forward kernel and of dfa_backward (no GPU needed;
+ * the bf16 dfa_forward refines it, see dfa_plan_describe_forward): the query
  * rows of each head are grouped by the set of (branch, segment) pairs that keep them and
  * cut into tiles; every tile carries its keys as arithmetic progressions: one per member
  * branch, or, where the member branches keep some keys more than once, the multiset union of
@@ -235,6 +236,24 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branc
                       const int32_t *head_offsets, int32_t *n_tiles, int32_t *n_rows,
                       int32_t *n_segs, int32_t *n_items, int32_t *tiles, int32_t *rows,
                       int32_t *segs, int32_t *items);
+
+/*
+ * The same view of the plan the bf16 dfa_forward launches.  It differs where row groups fill only part of a
+ * 256-row tile (small images: the rows of one window of the narrowest branch fall into several groups by which
+ * dilated branches also keep them): groups that share most of their keys are packed into one tile, each group
+ * on 64-row waves of its own, and the tile walks the union of their key lists once.  A progression then has a
+ * multiplicity per wave, 0 where that wave's rows do not attend to its keys (their scores are masked).
+ * Arguments as dfa_plan_describe, with
+ *   rows       an entry < 0 is a filler slot between two groups of a packed tile (it holds ~n of a row n of the
+ *              group before it; nothing is stored for it)
+ *   segs       [n_segs][4] = (first key, key stride, key count, largest multiplicity over the waves)
+ *   wave_mult  host int32 [n_segs][4]: multiplicity of the progression's keys for the rows of wave 0..3
+ *              (slots 64w .. 64w+63 of the tile); NULL to skip
+ */
+int dfa_plan_describe_forward(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branches, int32_t nb,
+                              const int32_t *head_offsets, int32_t *n_tiles, int32_t *n_rows,
+                              int32_t *n_segs, int32_t *n_items, int32_t *tiles, int32_t *rows,
+                              int32_t *segs, int32_t *wave_mult, int32_t *items);
 
 /*
  * Projection either side of the operator inside an encoder layer (the ViT self-attention

@@ -20,7 +20,7 @@ DFA_ERR_WORKSPACE = -8
 EXPORTS = [
     "dfa_version", "dfa_error_string", "dfa_index_map", "dfa_index_map_device", "dfa_workspace_bytes", "dfa_forward",
     "dfa_forward_static",
-    "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe",
+    "dfa_forward_branch", "dfa_merge", "dfa_gather", "dfa_scatter", "dfa_plan_describe", "dfa_plan_describe_forward",
     "dfa_release_plans", "dfa_linear", "dfa_encoder_stack", "dfa_backward",
 ]
 BENCH_EXPORTS = ["dfa_forward_timed", "dfa_mfma_peak", "dfa_dense_unfused", "dfa_dense_unfused_workspace_bytes"]
@@ -83,6 +83,8 @@ def lib():
         L.dfa_scatter.argtypes = [vp, i32, i32, i32, i32, ctypes.c_int, Branch, _i32p, vp, vp]
         L.dfa_plan_describe.argtypes = [i32, i32, i32, ctypes.POINTER(Branch), i32, _i32p,
                                         _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.dfa_plan_describe_forward.argtypes = [i32, i32, i32, ctypes.POINTER(Branch), i32, _i32p,
+                                                _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p]
         i64 = ctypes.c_int64
         L.dfa_linear.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
         L.dfa_encoder_stack.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, ctypes.POINTER(Branch), i32,
@@ -438,6 +440,28 @@ def plan_describe(B, H, N, branches, head_offsets=None):
     _check(lib().dfa_plan_describe(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(items)),
            "dfa_plan_describe")
     return dict(tiles=tiles, rows=rows, segs=segs[:ns], items=items)
+
+
+def plan_describe_forward(B, H, N, branches, head_offsets=None):
+    """Host view of the plan the bf16 forward launches (row groups packed into tiles): as plan_describe, plus
+    wave_mult [n_segs][4], the multiplicity of each progression for the rows of each wave of its tile."""
+    import numpy as np
+    br, nb = _branches(branches)
+    off = _i32_array(head_offsets)
+    cnt = [ctypes.c_int32(0) for _ in range(4)]
+    refs = [ctypes.byref(c) for c in cnt]
+    _check(lib().dfa_plan_describe_forward(B, H, N, br, nb, off, *refs, None, None, None, None, None),
+           "dfa_plan_describe_forward")
+    nt, nr, ns, ni = (c.value for c in cnt)
+    tiles = np.zeros((nt, 6), dtype=np.int32)
+    rows = np.zeros((nr,), dtype=np.int32)
+    segs = np.zeros((max(ns, 1), 4), dtype=np.int32)
+    wave_mult = np.zeros((max(ns, 1), 4), dtype=np.int32)
+    items = np.zeros((ni, 2), dtype=np.int32)
+    p = lambda a: a.ctypes.data_as(_i32p)
+    _check(lib().dfa_plan_describe_forward(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(wave_mult), p(items)),
+           "dfa_plan_describe_forward")
+    return dict(tiles=tiles, rows=rows, segs=segs[:ns], wave_mult=wave_mult[:ns], items=items)
 
 
 def release_plans():

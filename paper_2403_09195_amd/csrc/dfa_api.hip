@@ -34,6 +34,8 @@ struct DevicePlan {
     const int32_t* rows = nullptr;
     const KeySeg* segs = nullptr;
     const Item* items = nullptr;
+    const float* wave_mult = nullptr;   // plans of the bf16 forward only
+    bool packed_tiles = false;          // some tile packs several row groups: the kernel variant that reads wave_mult
     int32_t n_items = 0;
     int device = 0;
     size_t bytes = 0;
@@ -66,9 +68,10 @@ using PlanRef = std::shared_ptr<const DevicePlan>;
 // shares of a split launch, each part 256-byte aligned.
 struct PackedPlan {
     std::vector<char> bytes;
-    size_t off_segs = 0, off_items = 0, off_split_wgs = 0, off_item_parts = 0;
+    size_t off_segs = 0, off_items = 0, off_split_wgs = 0, off_item_parts = 0, off_wave_mult = 0;
     int32_t n_items = 0;
     int32_t n_split_wgs = 0;
+    bool packed_tiles = false;
 };
 
 constexpr int kPlanOrder = 3;              // launch order of build_plan (see dfa_plan.cpp)
@@ -82,22 +85,31 @@ size_t split_bytes(int32_t n_split_wgs) {
     return n_split_wgs > 0 ? align256((size_t)n_split_wgs * kSplitBlockFloats * sizeof(float)) : 0;
 }
 
+// packed: the plan of the bf16 forward kernel (row groups may share a tile, multiplicities per wave); the fp32 and
+// backward kernels read the plain one.
 int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, const int32_t* offsets,
-              const ChipShape& chip, PackedPlan* out) {
+              const ChipShape& chip, bool packed, PackedPlan* out) {
     HostPlan hp;
-    build_plan(B, H, N, br, nb, offsets, kPlanOrder, chip, &hp);
+    build_plan(B, H, N, br, nb, offsets, kPlanOrder, chip, packed, &hp);
     if (hp.items.size() > (size_t)0x7fffffff) return DFA_ERR_TOO_LARGE;
     const size_t b_rows = align256(hp.rows.size() * sizeof(int32_t));
     const size_t b_segs = align256(hp.segs.size() * sizeof(KeySeg) + sizeof(KeySeg));
     const size_t b_items = align256(hp.items.size() * sizeof(Item));
-    split_plan(&hp, chip);
+    if (packed) split_plan(&hp, chip);
     const size_t b_wgs = align256(hp.split_wgs.size() * sizeof(SplitWg));
     const size_t b_parts = align256(hp.item_parts.size() * sizeof(ItemParts));
-    out->bytes.assign(b_rows + b_segs + b_items + b_wgs + b_parts, 0);
+    const size_t b_wmult = packed ? align256((hp.segs.size() + 1) * kTileWaves * sizeof(float)) : 0;
+    out->bytes.assign(b_rows + b_segs + b_items + b_wgs + b_parts + b_wmult, 0);
     out->off_segs = b_rows;
     out->off_items = b_rows + b_segs;
     out->off_split_wgs = out->off_items + b_items;
     out->off_item_parts = out->off_split_wgs + b_wgs;
+    out->off_wave_mult = out->off_item_parts + b_parts;
+    if (packed) {
+        // log2 of the multiplicities, -inf where a wave's rows skip the progression
+        float* wm = reinterpret_cast<float*>(out->bytes.data() + out->off_wave_mult);
+        for (size_t x = 0; x < hp.wave_mult.size(); ++x) wm[x] = hp.wave_mult[x] > 0 ? std::log2((float)hp.wave_mult[x]) : -INFINITY;
+    }
     if (!hp.rows.empty()) std::memcpy(out->bytes.data(), hp.rows.data(), hp.rows.size() * sizeof(int32_t));
     if (!hp.segs.empty()) std::memcpy(out->bytes.data() + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg));
     if (!hp.items.empty()) std::memcpy(out->bytes.data() + b_rows + b_segs, hp.items.data(), hp.items.size() * sizeof(Item));
@@ -107,6 +119,7 @@ int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t n
     }
     out->n_items = (int32_t)hp.items.size();
     out->n_split_wgs = (int32_t)hp.split_wgs.size();
+    out->packed_tiles = hp.packed_tiles;
     return DFA_OK;
 }
 
@@ -122,11 +135,13 @@ void point_plan(DevicePlan* dp, void* base, const PackedPlan& pp, int device) {
     dp->split_wgs = reinterpret_cast<const SplitWg*>(b + pp.off_split_wgs);
     dp->item_parts = reinterpret_cast<const ItemParts*>(b + pp.off_item_parts);
     dp->n_split_wgs = pp.n_split_wgs;
+    dp->wave_mult = reinterpret_cast<const float*>(b + pp.off_wave_mult);
+    dp->packed_tiles = pp.packed_tiles;
 }
 
-std::vector<int32_t> plan_key(int device, int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-                              const int32_t* offsets) {
-    std::vector<int32_t> key = {device, B, H, N, nb, offsets ? 1 : 0};
+std::vector<int32_t> plan_key(int device, bool packed, int32_t B, int32_t H, int32_t N, const dfa_branch_t* br,
+                              int32_t nb, const int32_t* offsets) {
+    std::vector<int32_t> key = {device, packed ? 1 : 0, B, H, N, nb, offsets ? 1 : 0};
     for (int x = 0; x < nb; ++x) {
         key.push_back(br[x].w);
         key.push_back(br[x].r);
@@ -171,13 +186,13 @@ int current_chip(int* device, ChipShape* chip) {
 
 // Looks the plan of the current device up, building and uploading it on first use (the only device
 // allocation the library makes).  Plans pushed out of the cache are freed once no call holds them.
-int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
+int get_plan(bool packed, int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
              const int32_t* offsets, PlanRef* out) {
     int device = 0;
     ChipShape chip;
     int rc = current_chip(&device, &chip);
     if (rc != DFA_OK) return rc;
-    PlanKey key = plan_key(device, B, H, N, br, nb, offsets);
+    PlanKey key = plan_key(device, packed, B, H, N, br, nb, offsets);
     {
         std::lock_guard<std::mutex> lock(g_mu);
         auto it = g_plans.find(key);
@@ -189,7 +204,7 @@ int get_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb
     }
     // built outside the lock: two threads may both build a new shape, the second result replaces the first
     PackedPlan pp;
-    rc = pack_plan(B, H, N, br, nb, offsets, chip, &pp);
+    rc = pack_plan(B, H, N, br, nb, offsets, chip, packed, &pp);
     if (rc != DFA_OK) return rc;
     auto dp = std::make_shared<DevicePlan>();
     void* base = nullptr;
@@ -307,17 +322,17 @@ int launch_forward(const DevicePlan& dp, const void* q, const void* k, const voi
     p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
     p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
     p.out = out; p.lse = lse;
-    p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items;
+    p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items; p.wave_mult = dp.wave_mult;
     p.H = H; p.N = N; p.scale = scale;
     p.split_wgs = dp.split_wgs; p.item_parts = dp.item_parts; p.split_ws = split_ws;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (dt == DFA_BF16 && !out_f32 && dp.n_split_wgs > 0 && split_ws) {
         // few workgroups: partial results per share of the key walk, then their log-sum-exp merge
-        e = launch_fwd_bf16_split(p, dp.n_split_wgs, st);
+        e = launch_fwd_bf16_split(p, dp.n_split_wgs, dp.packed_tiles, st);
         if (e == hipSuccess) e = launch_merge_split(p, dp.n_items, st);
     } else if (dt == DFA_BF16) {
-        e = launch_fwd_bf16(p, dp.n_items, out_f32, st);
+        e = launch_fwd_bf16(p, dp.n_items, out_f32, dp.packed_tiles, st);
     } else {
         e = launch_fwd_f32(p, dp.n_items, st);         // fp32 inputs always give fp32 output
     }
@@ -332,7 +347,8 @@ int forward_impl(const void* q, const void* k, const void* v, dfa_strides_t sq, 
     if (rc != DFA_OK) return rc;
     if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return DFA_ERR_ALIGN;
     PlanRef dp;
-    rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+    // fp32 output from bf16 inputs is the unmerged single branch of dfa_forward_branch: the plain plan
+    rc = get_plan(dt == DFA_BF16 && !out_f32, B, H, N, branches, nb, head_offsets, &dp);
     if (rc != DFA_OK) return rc;
     float* split_ws = nullptr;
     if (workspace && dt == DFA_BF16 && !out_f32 && dp->n_split_wgs > 0) {
@@ -423,10 +439,10 @@ int dfa_forward_static(const void* q, const void* k, const void* v, dfa_strides_
             ss.ptr = static_cast<unsigned char*>(p);
             ss.plan.owned = false;
         }
-        PlanKey key = plan_key(device, B, H, N, branches, nb, head_offsets);
+        PlanKey key = plan_key(device, dt == DFA_BF16, B, H, N, branches, nb, head_offsets);
         if (!ss.holds_plan || ss.key != key) {
             PackedPlan pp;
-            rc = pack_plan(B, H, N, branches, nb, head_offsets, chip, &pp);
+            rc = pack_plan(B, H, N, branches, nb, head_offsets, chip, dt == DFA_BF16, &pp);
             if (rc != DFA_OK) return rc;
             const size_t plan_bytes = align256(pp.bytes.size());
             const size_t part_bytes = dt == DFA_BF16 ? split_bytes(pp.n_split_wgs) : 0;
@@ -538,7 +554,7 @@ int dfa_backward(const void* q, const void* k, const void* v, const void* out, c
     }
     try {
         PlanRef plan;
-        rc = get_plan(B, H, N, branches, nb, head_offsets, &plan);
+        rc = get_plan(false, B, H, N, branches, nb, head_offsets, &plan);
         if (rc != DFA_OK) return rc;
         const DevicePlan& dp = *plan;
         BwdParams p;
@@ -598,7 +614,7 @@ int dfa_encoder_stack(const void* x, const void* w_qkv, const void* w_o, int32_t
     if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return DFA_ERR_ALIGN;
     try {
         PlanRef dp;
-        rc = get_plan(B, H, N, branches, nb, head_offsets, &dp);
+        rc = get_plan(true, B, H, N, branches, nb, head_offsets, &dp);
         if (rc != DFA_OK) return rc;
         if (workspace && dp->n_split_wgs > 0 && workspace_bytes < split_bytes(dp->n_split_wgs))
             return DFA_ERR_WORKSPACE;
@@ -627,7 +643,7 @@ size_t dfa_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype
         ChipShape chip;                    // the MI355X when no device can be asked
         if (current_chip(&device, &chip) != DFA_OK) (void)hipGetLastError();
         HostPlan hp;
-        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, chip, &hp);
+        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, chip, true, &hp);
         split_plan(&hp, chip);
         return split_bytes((int32_t)hp.split_wgs.size());
     } catch (const std::bad_alloc&) {
@@ -635,16 +651,18 @@ size_t dfa_workspace_bytes(int32_t B, int32_t H, int32_t N, int32_t D, dfa_dtype
     }
 }
 
-int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
-                      const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
-                      int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* items) {
+namespace {
+
+int describe_plan(bool packed, int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
+                  const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
+                  int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* wave_mult, int32_t* items) {
     if (!n_tiles || !n_rows || !n_segs || !n_items) return DFA_ERR_NULL;
     if (B <= 0) return DFA_ERR_SHAPE;
     const int rc = check_branches(H, N, branches, nb, head_offsets);
     if (rc != DFA_OK) return rc;
     try {
         HostPlan hp;
-        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, ChipShape(), &hp);
+        build_plan(B, H, N, branches, nb, head_offsets, kPlanOrder, ChipShape(), packed, &hp);
         *n_tiles = (int32_t)hp.tiles.size();
         *n_rows = (int32_t)hp.rows.size();
         *n_segs = (int32_t)hp.segs.size();
@@ -663,6 +681,7 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
                 segs[4 * s + 2] = hp.segs[s].count;
                 segs[4 * s + 3] = hp.seg_mult[s];
             }
+        if (wave_mult) std::memcpy(wave_mult, hp.wave_mult.data(), hp.wave_mult.size() * sizeof(int32_t));
         if (items)
             for (size_t i = 0; i < hp.items.size(); ++i) {
                 items[2 * i] = hp.items[i].tile;
@@ -672,6 +691,23 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
         return DFA_ERR_LAUNCH;
     }
     return DFA_OK;
+}
+
+}  // namespace
+
+int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
+                      const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
+                      int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* items) {
+    return describe_plan(false, B, H, N, branches, nb, head_offsets, n_tiles, n_rows, n_segs, n_items, tiles, rows, segs,
+                         nullptr, items);
+}
+
+int dfa_plan_describe_forward(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
+                              const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
+                              int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* wave_mult,
+                              int32_t* items) {
+    return describe_plan(true, B, H, N, branches, nb, head_offsets, n_tiles, n_rows, n_segs, n_items, tiles, rows, segs,
+                         wave_mult, items);
 }
 
 int dfa_release_plans(void) {

@@ -28,6 +28,9 @@ struct FwdParams {
     const int32_t* rows;
     const KeySeg* segs;
     const Item* items;
+    // bf16 kernel only: log2 of the multiplicity of each progression's keys for the rows of each of the tile's four
+    // waves, [segs][4]; -inf = the wave's rows do not attend to these keys (tiles that pack several row groups)
+    const float* wave_mult;
     int32_t H, N;
     float scale;        // multiplies q.k
     // Split launches only (few workgroups, see launch_fwd_bf16_split): workgroup g walks the share of a tile's
@@ -80,8 +83,8 @@ __device__ __forceinline__ int32_t segment_first(int32_t i, int32_t w, int32_t o
 }
 
 // Launchers (defined in the .hip files); every one returns the hipError_t of the launch.
-hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st);
-hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, hipStream_t st);
+hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, bool packed, hipStream_t st);
+hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, bool packed, hipStream_t st);
 hipError_t launch_merge_split(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdParams& p, int n_items, hipStream_t st);
 hipError_t launch_bwd(const BwdParams& p, int n_items, int32_t B, bool bf16, hipStream_t st);

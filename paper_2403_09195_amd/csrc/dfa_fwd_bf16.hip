@@ -91,6 +91,8 @@ __device__ __forceinline__ void issue_stage(const FwdParams& p, const uint16_t* 
 // If a lane's partial row sum of one 32-key block exceeds this, some exponent may have left
 // the comfortable range and the reference exponent is moved up (see rebase_block).
 constexpr float kRebaseThreshold = 256.0f;
+// Reference exponent before the first score of a row: far below any scaled score of finite inputs.
+constexpr float kRefStart = -1.0e30f;
 
 // Softmax numerators of one 32-key block against the current reference exponents m_ref (no
 // row maximum is taken here): p = exp2(c*s - m_ref), rounded to bf16 (nearest even) and packed
@@ -280,13 +282,17 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
 
 // kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves an fp32
 // partial result (rows in tile order) in its own block of the workspace; OutT is float then.
-template <typename OutT, bool kSplit>
+// kPacked: the plan has tiles that pack several row groups (multiplicities per wave, filler slots); plans without
+// such tiles run the variant that has none of that in its way.
+template <typename OutT, bool kSplit, bool kPacked>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void dfa_fwd_bf16_kernel(const FwdParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t k_lds[kStages][kStageElems];
     __shared__ __attribute__((aligned(1024))) uint16_t v_lds[kStages][kStageElems];
-    __shared__ int32_t row_idx[kTileRows];
-    __shared__ KeySeg seg_lds[kMaxTileSegs];
+    __shared__ int32_t row_idx[kTileRows];      // token of each slot; < 0: a filler slot, nothing to store
+    // the tile's key progressions, one copy per wave: log2_mult of wave w's copy is the figure for w's rows
+    // (-inf: they do not attend to the progression's keys)
+    __shared__ KeySeg seg_all[kPacked ? 4 : 1][kMaxTileSegs];
 
     int part = 0, nparts = 1, item_index = blockIdx.x;
     if (kSplit) {
@@ -308,12 +314,20 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // longest wait, and the set-up of the K/V stages below runs under it.  (The plan's progression
     // array ends with one spare entry, so a tile without progressions still reads inside it.)
     const int32_t my_row = p.rows[tile.row_begin + min(tid, tile.nrows - 1)];
-    const int32_t q_row[2] = {p.rows[tile.row_begin + min(wave * 64 + j, tile.nrows - 1)],
-                              p.rows[tile.row_begin + min(wave * 64 + 32 + j, tile.nrows - 1)]};
+    int32_t q_row[2] = {p.rows[tile.row_begin + min(wave * 64 + j, tile.nrows - 1)],
+                        p.rows[tile.row_begin + min(wave * 64 + 32 + j, tile.nrows - 1)]};
+    // a filler slot of a packed tile holds ~n of a row n of its group: loaded like any row, never stored
+    if (kPacked) {
+        q_row[0] ^= q_row[0] >> 31;
+        q_row[1] ^= q_row[1] >> 31;
+    }
     KeySeg my_seg = p.segs[tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)];
-    // held here so that the compiler does not move this load behind the Q loads (whose wait would then
+    float4 my_wmult = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (kPacked) my_wmult = *reinterpret_cast<const float4*>(p.wave_mult + 4 * (int64_t)(tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)));
+    // held here so that the compiler does not move these loads behind the Q loads (whose wait would then
     // sit in front of the barrier)
     asm volatile("" : "+v"(my_seg.key0), "+v"(my_seg.stride), "+v"(my_seg.count), "+v"(my_seg.log2_mult));
+    if (kPacked) asm volatile("" : "+v"(my_wmult.x), "+v"(my_wmult.y), "+v"(my_wmult.z), "+v"(my_wmult.w));
     // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
     bf16x8 qf[2][4];
     {
@@ -325,7 +339,17 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
                 qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + (int64_t)q_row[qb] * p.sqn + 16 * kk + 8 * g);
     }
     row_idx[tid] = my_row;
-    if (tid < tile.nseg) seg_lds[tid] = my_seg;
+    if (tid < tile.nseg) {
+        if constexpr (kPacked) {
+            my_seg.log2_mult = my_wmult.x; seg_all[0][tid] = my_seg;
+            my_seg.log2_mult = my_wmult.y; seg_all[1][tid] = my_seg;
+            my_seg.log2_mult = my_wmult.z; seg_all[2][tid] = my_seg;
+            my_seg.log2_mult = my_wmult.w; seg_all[3][tid] = my_seg;
+        } else {
+            seg_all[0][tid] = my_seg;
+        }
+    }
+    const KeySeg* const seg_lds = seg_all[kPacked ? wave : 0];
     __syncthreads();
 
     OutT* const out = static_cast<OutT*>(p.out);
@@ -446,7 +470,10 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // A progression whose keys count m times adds log2(m) to its scaled scores.  That is done by holding
     // m_ref as (reference exponent - log2 m of the progression being walked) and moving it when the
     // walk enters a progression of another multiplicity; sums and accumulator stay on the true reference.
-    float m_ref[2] = {-INFINITY, -INFINITY};
+    // The start value is finite (any score moves the reference up to itself at once, the factor exp2(start - new)
+    // being an exact 0): a wave whose rows skip the first progressions of a packed tile sees only masked scores
+    // there, and -inf - start is a clean -inf where -inf - -inf would not be.
+    float m_ref[2] = {kPacked ? kRefStart : -INFINITY, kPacked ? kRefStart : -INFINITY};
     float l_run[2] = {0.f, 0.f};               // running sum of the row (the two lanes of a query hold the same value)
     float bias_cur = 0.f;                      // log2 m held in m_ref (wave-uniform)
 
@@ -476,13 +503,16 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     float psum[2];
     int stage = 0;
     int nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
-    // a progression whose keys count m times: log2 m comes off the reference exponents held in m_ref
+    // a progression whose keys count m times for this wave's rows: log2 m comes off the reference exponents held
+    // in m_ref; m = 0 (log2 m = -inf): the rows do not attend to these keys, every score of the step is masked
     auto enter_step = [&]() {
-        nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
-        if (cur.bias != bias_cur) {            // both blocks of this step still hold raw scores
-            m_ref[0] -= cur.bias - bias_cur;
-            m_ref[1] -= cur.bias - bias_cur;
-            bias_cur = cur.bias;
+        const bool attends = !kPacked || cur.bias > -INFINITY;
+        nvalid = attends ? min(kKeyTile, cur.count - cur.t * kKeyTile) : 0;
+        const float bias = attends ? cur.bias : bias_cur;
+        if (bias != bias_cur) {                // both blocks of this step still hold raw scores
+            m_ref[0] -= bias - bias_cur;
+            m_ref[1] -= bias - bias_cur;
+            bias_cur = bias;
         }
     };
     enter_step();
@@ -545,7 +575,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const float lse_row = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
         if (kSplit) {
             if (g_e == 0) blk[kTileRows * kD + slot] = slot < tile.nrows ? lse_row : -INFINITY;
-        } else if (lse_out && g_e == 0 && slot < tile.nrows) {
+        } else if (lse_out && g_e == 0 && slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
             lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = lse_row;
         }
     }
@@ -574,7 +604,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             for (int s = 0; s < 8; ++s) {
                 const int row = 8 * s + srow, slot = wave * 64 + row;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
-                if (slot < tile.nrows) {
+                if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
                     const int64_t n = row_idx[slot];
                     *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(out + (out_bh + n * p.H) * kD) + 16 * schunk) = val;
                 }
@@ -584,7 +614,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int slot = wave * 64 + qb * 32 + j_e;
-            if (slot < tile.nrows) {
+            if (slot < tile.nrows && (kSplit || !kPacked || row_idx[slot] >= 0)) {
                 const int64_t n = row_idx[slot];
                 OutT* op = kSplit ? reinterpret_cast<OutT*>(blk) + slot * kD : out + (out_bh + n * p.H) * kD;
 #pragma unroll
@@ -612,6 +642,7 @@ __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
     const ItemParts ip = p.item_parts[blockIdx.x];
     const float* blk0 = p.split_ws + (int64_t)ip.first_wg * kSplitBlockFloats;
     const int32_t n = p.rows[tile.row_begin + r];
+    if (n < 0) return;                  // filler slot of a packed tile
     float lb[kMaxSplit];
     float4 o[kMaxSplit];
 #pragma unroll
@@ -654,19 +685,25 @@ __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
 
 }  // namespace
 
-hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, hipStream_t st) {
+hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, bool packed, hipStream_t st) {
+    if (out_f32 && packed) return hipErrorInvalidValue;      // fp32 output is launched on plain plans only
     if (out_f32)
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, false>), dim3(n_items), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, false, false>), dim3(n_items), dim3(256), 0, st, p);
+    else if (packed)
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, false, true>), dim3(n_items), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, false>), dim3(n_items), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, false, false>), dim3(n_items), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
 // Launches with few workgroups are bound by the longest tile's walk, not by throughput: there the tiles are walked by
 // several workgroups each (p.split_wgs), every one over a share of the steps, into fp32 partial results (p.split_ws)
 // that launch_merge_split combines.
-hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, hipStream_t st) {
-    hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, bool packed, hipStream_t st) {
+    if (packed)
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

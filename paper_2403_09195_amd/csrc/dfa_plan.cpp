@@ -1,6 +1,7 @@
 #include "dfa_plan.h"
 
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <map>
 #include <numeric>
@@ -15,16 +16,23 @@ int64_t steps_of(const std::vector<KeySeg>& segs) {
     return n;
 }
 
-// The multiset union of the progressions in `plain` (one per member branch of a tile) rewritten
-// as progressions in which every key has one multiplicity.  With L the least common multiple of
-// the strides, a residue class mod L is either inside or outside each progression's own class,
-// so along one class the multiplicity only changes where a progression starts or ends.  Classes
-// covered by the same progressions are joined into coarser strides where they line up.
-// Returns false (outputs untouched) when L is too large, the list would not fit a tile, or no
-// 64-key step would be saved.
-bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::vector<int32_t>* out_mult) {
-    const int ns = (int)plain.size();
-    if (ns < 2) return false;
+// Multiplicities of one progression's keys for the (up to kTileWaves) row groups of a tile; 0 = the group's rows
+// do not attend to these keys.
+using MultVec = std::array<int32_t, kTileWaves>;
+
+// The multiset union of the progressions in `plain` rewritten as progressions in which every key has one
+// multiplicity.  A tile of one row group has one plain progression per member branch; a tile that packs several
+// row groups has the distinct progressions of all of them, and member[g] says which ones group g's rows attend
+// to (bit x = plain[x]): a key's multiplicity is then a number per group.  With L the least common multiple of
+// the strides, a residue class mod L is either inside or outside each progression's own class, so along one
+// class the multiplicities only change where a progression starts or ends.  Classes covered by the same
+// progressions are joined into coarser strides where they line up.
+// Returns false (outputs untouched) when L is too large, the list would not fit a tile, or no 64-key step
+// would be saved against walking the plain progressions one after the other.
+bool coalesce(const std::vector<KeySeg>& plain, const std::vector<uint32_t>& member, std::vector<KeySeg>* out,
+              std::vector<MultVec>* out_mult) {
+    const int ns = (int)plain.size(), ng = (int)member.size();
+    if (ns < 2 || ns > 32) return false;
     int64_t L = 1;
     for (const KeySeg& s : plain) {
         L = std::lcm<int64_t>(L, s.stride);
@@ -39,7 +47,7 @@ bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::v
             if ((rho - plain[x].key0) % plain[x].stride == 0) mask_of[rho] |= 1u << x;
 
     std::vector<KeySeg> segs;
-    std::vector<int32_t> mult;
+    std::vector<MultVec> mult;
     std::vector<char> used(L, 0);
     for (int64_t rho0 = 0; rho0 < L; ++rho0) {
         const uint32_t mask = mask_of[rho0];
@@ -64,10 +72,12 @@ bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::v
                 size_t open = segs.size();                      // pieces of this (a mod g) start here
                 for (size_t c = 0; c + 1 < cuts.size(); ++c) {
                     const int64_t lo = cuts[c], hi = cuts[c + 1];
-                    int32_t m = 0;
+                    uint32_t cover = 0;                             // progressions that hold the keys of [lo, hi) in these classes
                     for (int x = 0; x < ns; ++x)
-                        if ((mask >> x & 1) && plain[x].key0 <= lo && hi - 1 <= last[x]) ++m;
-                    if (m == 0) continue;
+                        if ((mask >> x & 1) && plain[x].key0 <= lo && hi - 1 <= last[x]) cover |= 1u << x;
+                    if (cover == 0) continue;
+                    MultVec m{};
+                    for (int gi = 0; gi < ng; ++gi) m[gi] = __builtin_popcount(cover & member[gi]);
                     const int64_t key0 = lo + (((a - lo) % g) + g) % g;
                     if (key0 >= hi) continue;
                     const int32_t count = (int32_t)((hi - 1 - key0) / g + 1);
@@ -75,7 +85,7 @@ bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::v
                         segs.back().key0 + (int64_t)segs.back().count * g == key0) {
                         segs.back().count += count;             // the progression runs on with the same multiplicity
                     } else {
-                        segs.push_back(KeySeg{(int32_t)key0, (int32_t)g, count, std::log2((float)m)});
+                        segs.push_back(KeySeg{(int32_t)key0, (int32_t)g, count, std::log2((float)std::max(m[0], 1))});
                         mult.push_back(m);
                     }
                 }
@@ -93,6 +103,43 @@ bool coalesce(const std::vector<KeySeg>& plain, std::vector<KeySeg>* out, std::v
         out->push_back(segs[i]);
         out_mult->push_back(mult[i]);
     }
+    return true;
+}
+
+// Rows of one head that share their key lists: the same parts of the same branches keep them.
+struct RowGroup {
+    std::vector<int32_t> rows;
+    std::vector<KeySeg> plain;        // one progression per member branch
+    std::vector<int64_t> plain_id;    // which (branch, part) each one is
+    std::vector<KeySeg> list;         // what a tile of these rows alone walks
+    std::vector<MultVec> list_mult;   // entry 0: the multiplicity of the progression's keys
+};
+
+int waves_of(const RowGroup& g) { return ((int)g.rows.size() + kWaveRows - 1) / kWaveRows; }
+
+// Key list of a tile whose rows come from the groups in `pack` (group i of the pack = entry i of the
+// multiplicities): the coalesced union of their progressions where that saves steps, else the distinct
+// progressions one after the other.  False when the list would not fit a tile.
+bool tile_list(const std::vector<const RowGroup*>& pack, std::vector<KeySeg>* list, std::vector<MultVec>* mult) {
+    std::vector<KeySeg> plain;
+    std::vector<int64_t> ids;
+    std::vector<uint32_t> member(pack.size(), 0);
+    for (size_t gi = 0; gi < pack.size(); ++gi)
+        for (size_t x = 0; x < pack[gi]->plain.size(); ++x) {
+            size_t at = std::find(ids.begin(), ids.end(), pack[gi]->plain_id[x]) - ids.begin();
+            if (at == ids.size()) {
+                if (ids.size() == 32) return false;
+                ids.push_back(pack[gi]->plain_id[x]);
+                plain.push_back(pack[gi]->plain[x]);
+            }
+            member[gi] |= 1u << at;
+        }
+    if (coalesce(plain, member, list, mult)) return true;
+    if ((int)plain.size() > kMaxTileSegs) return false;
+    list->assign(plain.begin(), plain.end());
+    mult->assign(plain.size(), MultVec{});
+    for (size_t x = 0; x < plain.size(); ++x)
+        for (size_t gi = 0; gi < pack.size(); ++gi) (*mult)[x][gi] = member[gi] >> x & 1;
     return true;
 }
 
@@ -115,19 +162,36 @@ int check_branches(int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb, con
 }
 
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-                const int32_t* offsets, int order_mode, const ChipShape& chip, HostPlan* plan) {
+                const int32_t* offsets, int order_mode, const ChipShape& chip, bool pack, HostPlan* plan) {
     const int kNumXcd = std::max(chip.dies, 1);
     const int kSlotsPerDie = std::max(chip.fwd_slots_per_die(), 1);
     plan->tiles.clear();
     plan->rows.clear();
     plan->segs.clear();
     plan->seg_mult.clear();
+    plan->wave_mult.clear();
     plan->items.clear();
+    plan->packed_tiles = false;
 
     std::vector<int64_t> tile_cost;   // (query, key) pairs of each tile
+    // appends a key list; wave_group[w] = which entry of a progression's multiplicities wave w's rows take (-1: none)
+    auto add_list = [&](const std::vector<KeySeg>& list, const std::vector<MultVec>& mult, const int (&wave_group)[kTileWaves]) {
+        const int32_t seg_begin = (int32_t)plan->segs.size();
+        plan->segs.insert(plan->segs.end(), list.begin(), list.end());
+        for (const MultVec& m : mult) {
+            int32_t most = 0;
+            for (int w = 0; w < kTileWaves; ++w) {
+                const int32_t mw = wave_group[w] < 0 ? 0 : m[wave_group[w]];
+                plan->wave_mult.push_back(mw);
+                most = std::max(most, mw);
+            }
+            plan->seg_mult.push_back(most);
+        }
+        return seg_begin;
+    };
     for (int32_t h = 0; h < H; ++h) {
-        // signature of a row: for each branch the segment that keeps it, or -1
-        std::map<std::vector<int32_t>, std::vector<int32_t>> groups;
+        // signature of a row: for each branch the part that keeps it, or -1
+        std::map<std::vector<int32_t>, RowGroup> by_sig;
         std::vector<int32_t> sig(nb);
         for (int32_t n = 0; n < N; ++n) {
             for (int x = 0; x < nb; ++x) {
@@ -135,14 +199,12 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 const int32_t part = n / br[x].w, pos = n - part * br[x].w - o;   // position inside the part
                 sig[x] = (pos >= 0 && pos % br[x].r == 0) ? part : -1;
             }
-            groups[sig].push_back(n);
+            by_sig[sig].rows.push_back(n);
         }
-        for (const auto& g : groups) {
-            const std::vector<int32_t>& s = g.first;
-            const std::vector<int32_t>& rows = g.second;
-            const int32_t seg_begin = (int32_t)plan->segs.size();
-            std::vector<KeySeg> list;
-            std::vector<int32_t> list_mult;
+        std::vector<RowGroup*> groups;
+        for (auto& kv : by_sig) {
+            const std::vector<int32_t>& s = kv.first;
+            RowGroup& g = kv.second;
             for (int x = 0; x < nb; ++x) {
                 if (s[x] < 0) continue;
                 const int32_t o = head_offset(offsets, H, x, h, br[x].r);
@@ -151,30 +213,95 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 const int64_t first = (int64_t)s[x] * br[x].w + o;
                 const int64_t end = std::min<int64_t>((int64_t)(s[x] + 1) * br[x].w, N);
                 const int32_t count = (int32_t)((end - 1 - first) / br[x].r + 1);   // >= 1: a row of the part is kept
-                list.push_back(KeySeg{(int32_t)first, br[x].r, count, 0.f});
-                list_mult.push_back(1);
+                g.plain.push_back(KeySeg{(int32_t)first, br[x].r, count, 0.f});
+                g.plain_id.push_back((int64_t)x * ((int64_t)N + 1) + s[x]);
             }
             // keys that several member branches keep are visited once, weighted by how many keep them
-            {
-                std::vector<KeySeg> merged;
-                std::vector<int32_t> merged_mult;
-                if (coalesce(list, &merged, &merged_mult)) {
-                    list.swap(merged);
-                    list_mult.swap(merged_mult);
+            if (!g.plain.empty()) tile_list({&g}, &g.list, &g.list_mult);
+            groups.push_back(&g);
+        }
+
+        // Row groups that fill only part of a tile.  Where such groups attend to many of the same keys (rows of one
+        // window of a narrow branch that differ in which wider, dilated branches also keep them), a tile takes
+        // several of them, each in waves of its own: the tile walks the union of their lists once, and a wave whose
+        // rows do not attend to a progression masks its scores (multiplicity 0).  A group joins a tile when at least
+        // half the steps of the shorter of the two lists are saved.
+        const size_t G = groups.size();
+        std::vector<char> done(G, 0);
+        for (size_t i = 0; i < G; ++i) {
+            if (done[i]) continue;
+            done[i] = 1;
+            const RowGroup& g = *groups[i];
+            const bool small = pack && !g.plain.empty() && waves_of(g) < kTileWaves;
+            std::vector<const RowGroup*> members = {&g};
+            std::vector<KeySeg> list = g.list;
+            std::vector<MultVec> list_mult = g.list_mult;
+            int waves = waves_of(g);
+            while (small && waves < kTileWaves) {
+                int64_t best = -1, best_saved = 0;
+                std::vector<KeySeg> best_list;
+                std::vector<MultVec> best_mult;
+                const int64_t have = steps_of(list);
+                for (size_t j = i + 1; j < std::min(G, i + 1 + kPackWindow); ++j) {
+                    const RowGroup& c = *groups[j];
+                    if (done[j] || c.plain.empty() || waves + waves_of(c) > kTileWaves) continue;
+                    std::vector<const RowGroup*> trial = members;
+                    trial.push_back(&c);
+                    std::vector<KeySeg> tl;
+                    std::vector<MultVec> tm;
+                    if (!tile_list(trial, &tl, &tm)) continue;
+                    const int64_t own = steps_of(c.list), saved = have + own - steps_of(tl);
+                    if (saved * 2 < std::min(have, own) || saved <= best_saved) continue;
+                    best = (int64_t)j;
+                    best_saved = saved;
+                    best_list.swap(tl);
+                    best_mult.swap(tm);
                 }
+                if (best < 0) break;
+                done[best] = 1;
+                members.push_back(groups[best]);
+                waves += waves_of(*groups[best]);
+                list.swap(best_list);
+                list_mult.swap(best_mult);
             }
             const int32_t nseg = (int32_t)list.size();
-            int64_t keys = 0;
-            for (const KeySeg& sg : list) keys += sg.count;
-            plan->segs.insert(plan->segs.end(), list.begin(), list.end());
-            plan->seg_mult.insert(plan->seg_mult.end(), list_mult.begin(), list_mult.end());
-            for (size_t lo = 0; lo < rows.size(); lo += kTileRows) {
-                const int32_t cnt = (int32_t)std::min<size_t>(kTileRows, rows.size() - lo);
-                Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, (int32_t)steps_of(list)};
-                plan->rows.insert(plan->rows.end(), rows.begin() + lo, rows.begin() + lo + cnt);
-                plan->tiles.push_back(t);
-                tile_cost.push_back(keys * cnt);
+            if (members.size() == 1) {
+                // tiles of one group: cut its rows into tiles that share the list; every wave takes entry 0
+                const int wave_group[kTileWaves] = {0, 0, 0, 0};
+                const int32_t seg_begin = add_list(list, list_mult, wave_group);
+                int64_t keys = 0;
+                for (const KeySeg& sg : list) keys += sg.count;
+                for (size_t lo = 0; lo < g.rows.size(); lo += kTileRows) {
+                    const int32_t cnt = (int32_t)std::min<size_t>(kTileRows, g.rows.size() - lo);
+                    Tile t{h, (int32_t)plan->rows.size(), cnt, seg_begin, nseg, (int32_t)steps_of(list)};
+                    plan->rows.insert(plan->rows.end(), g.rows.begin() + lo, g.rows.begin() + lo + cnt);
+                    plan->tiles.push_back(t);
+                    tile_cost.push_back(keys * cnt);
+                }
+                continue;
             }
+            // one tile of several groups: each starts on a wave of its own; the slots between the end of a group and
+            // the next wave hold ~row of the group's last row (a valid row to load, never stored)
+            plan->packed_tiles = true;
+            int wave_group[kTileWaves] = {-1, -1, -1, -1};
+            const int32_t row_begin = (int32_t)plan->rows.size();
+            int w0 = 0;
+            int64_t pairs = 0;
+            for (size_t gi = 0; gi < members.size(); ++gi) {
+                const RowGroup& m = *members[gi];
+                if (gi > 0) {
+                    const int32_t filler = ~members[gi - 1]->rows.back();
+                    while ((int32_t)plan->rows.size() - row_begin < w0 * kWaveRows) plan->rows.push_back(filler);
+                }
+                plan->rows.insert(plan->rows.end(), m.rows.begin(), m.rows.end());
+                for (int w = 0; w < waves_of(m); ++w) wave_group[w0 + w] = (int)gi;
+                w0 += waves_of(m);
+                for (size_t x = 0; x < list.size(); ++x)
+                    pairs += (int64_t)list[x].count * (list_mult[x][gi] ? 1 : 0) * (int64_t)m.rows.size();
+            }
+            const int32_t seg_begin = add_list(list, list_mult, wave_group);
+            plan->tiles.push_back(Tile{h, row_begin, (int32_t)plan->rows.size() - row_begin, seg_begin, nseg, (int32_t)steps_of(list)});
+            tile_cost.push_back(pairs);
         }
     }
 

@@ -13,6 +13,9 @@
 namespace dfa {
 
 constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
+constexpr int kTileWaves = 4;
+constexpr int kWaveRows = 64;
+constexpr int kPackWindow = 32;  // row groups (in signature order) after a group that are tried as its tile mates
 constexpr int kFwdWorkgroupsPerCu = 2;   // workgroups of the bf16 forward kernel that fit one compute unit
 constexpr int kTailItemsPerDie = 96;     // launch order: items at the end of a die's list that go heaviest first
 constexpr int kMaxTileSegs = 32; // key progressions per tile (the kernels hold a tile's list in LDS)
@@ -30,7 +33,7 @@ struct KeySeg {
 struct Tile {
     int32_t h;          // head
     int32_t row_begin;  // first entry in the row list
-    int32_t nrows;      // 1 .. kTileRows
+    int32_t nrows;      // 1 .. kTileRows: slots of the tile (a packed tile's list has entries < 0, see HostPlan::rows)
     int32_t seg_begin;  // first entry in the key-segment list
     int32_t nseg;       // 0 = rows kept by no branch (output 0, lse -inf)
     int32_t n_steps;    // 64-key steps of the whole list: sum of ceil(count / 64)
@@ -67,9 +70,13 @@ constexpr int kMinShareSteps = 8;        // a share of fewer 64-key steps is not
 
 struct HostPlan {
     std::vector<Tile> tiles;
+    // token positions, tile after tile.  A tile that packs several row groups starts each group on a wave of its
+    // own; the slots in between hold ~n of a row n of the group (valid to load, never stored).
     std::vector<int32_t> rows;
     std::vector<KeySeg> segs;
-    std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs
+    std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs (packed tiles: the largest of its waves)
+    std::vector<int32_t> wave_mult;  // [segs][kTileWaves]: multiplicity for the rows of each wave, 0 = they skip the keys
+    bool packed_tiles = false;       // some tile packs several row groups (wave_mult differs between waves, filler slots)
     std::vector<Item> items;
     std::vector<SplitWg> split_wgs;      // empty: the launch is not split
     std::vector<ItemParts> item_parts;
@@ -85,8 +92,10 @@ inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t
 
 // Builds tiles, row lists, key segments and the launch order for B images.
 // order_mode: 3 = default (see dfa_plan.cpp), 0 to 2 are alternatives kept for measurement.
+// pack: row groups of fewer than four waves may share a tile (only the bf16 forward kernel reads such tiles:
+// it takes its multiplicities per wave from wave_mult).
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
-                const int32_t* offsets, int order_mode, const ChipShape& chip, HostPlan* plan);
+                const int32_t* offsets, int order_mode, const ChipShape& chip, bool pack, HostPlan* plan);
 
 // Launches of the bf16 forward kernel with fewer workgroups than half the chip's slots are as long as their longest
 // tile's walk.  There the walks are cut: every tile gets one workgroup, then the workgroup slots left over go one by

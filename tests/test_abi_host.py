@@ -312,6 +312,93 @@ def test_plan_of_random_problems(B, seed):
     assert len(items) % 8 == 0 and len(set(map(tuple, real.tolist()))) == len(real) == len(tiles) * Bsz
 
 
+def _check_forward_plan(B, Bsz, H, N, branches, offs, sample=None):
+    """The plan of the bf16 forward: every (h, n) is stored by exactly one slot, and for every slot (filler slots
+    included: they are computed like the row they repeat) the progressions its wave takes, with the wave's
+    multiplicities, add up to exactly the multiset of keys the definition gives the row."""
+    p = B.plan_describe_forward(Bsz, H, N, branches, offs)
+    tiles, rows, segs, wm, items = p["tiles"], p["rows"], p["segs"], p["wave_mult"], p["items"]
+    seen = np.zeros((H, N), dtype=np.int32)
+    for (h, rb, nr, sb, ns, steps) in tiles:
+        assert 1 <= nr <= 256 and ns <= 32
+        assert steps == sum((int(c) + 63) // 64 for c in segs[sb:sb + ns, 2])
+        tile_rows = rows[rb:rb + nr]
+        assert tile_rows[0] >= 0 and tile_rows[-1] >= 0
+        real = tile_rows[tile_rows >= 0]
+        seen[h, real] += 1
+        if ns:
+            live = wm[sb:sb + ns, :(nr + 63) // 64]
+            assert live.max(axis=0).min() >= 1 and live.max(axis=1).min() >= 1    # no idle wave, no unused progression
+            assert np.array_equal(segs[sb:sb + ns, 3], wm[sb:sb + ns].max(axis=1))
+            assert np.all(wm[sb:sb + ns, (nr + 63) // 64:] == 0) or np.all(tile_rows >= 0)
+        slots = range(nr) if sample is None else sample(nr)
+        for slot in slots:
+            n = int(tile_rows[slot])
+            n = ~n if n < 0 else n
+            w = slot // 64
+            got = [(int(segs[s][0]), int(segs[s][1]), int(segs[s][2]), int(wm[s][w])) for s in range(sb, sb + ns) if wm[s][w] > 0]
+            counts, _ = _expected_multiset(N, h, n, branches, offs)
+            mine = np.zeros(N, dtype=np.int32)
+            for (first, stride, count, mult) in got:
+                assert count >= 1 and stride >= 1 and 0 <= first and first + stride * (count - 1) < N
+                mine[first:first + stride * count:stride] += mult
+            assert np.array_equal(mine, counts), (h, n, slot)
+    assert np.all(seen == 1)
+    real = items[items[:, 0] >= 0]
+    assert len(items) % 8 == 0 and len(set(map(tuple, real.tolist()))) == len(real) == len(tiles) * Bsz
+    return p
+
+
+@pytest.mark.parametrize("Bsz,H,N,branches,offs", [
+    (1, 1, 256, [(64, 2)], None),
+    (16, 6, 256, [(64, 1), (128, 2), (256, 4)], None),
+    (16, 12, 1024, [(256, 1), (512, 2), (1024, 4)], None),
+    (1, 12, 4096, [(1024, 1), (2048, 2), (4096, 4)], None),
+    (3, 4, 360, [(120, 3), (180, 2), (360, 5)], [[2, 0, 1, 2], [1, 1, 0, 0], [4, 3, 0, 1]]),
+    (40, 2, 96, [(32, 4), (96, 1)], None),
+    (2, 3, 50, [(16, 3), (7, 2), (64, 5)], None),
+    (1, 2, 1025, [(1024, 1), (300, 7)], [[0, 0], [6, 2]]),
+    (1, 2, 512, [(256, 2), (256, 2), (512, 1)], None),
+    (2, 2, 700, [(100, 1), (350, 2), (700, 3), (50, 1)], None),
+])
+def test_forward_plan_covers_the_definition(B, Bsz, H, N, branches, offs):
+    _check_forward_plan(B, Bsz, H, N, branches, offs)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_forward_plan_of_random_problems(B, seed):
+    rng = np.random.default_rng(150 + seed)
+    Bsz, H, N, nb = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(1, 700)), int(rng.integers(1, 9))
+    branches, offs = [], []
+    for _ in range(nb):
+        r = int(rng.integers(1, 8))
+        branches.append((int(rng.integers(1, 2 * N + 1)), r))
+        offs.append([int(rng.integers(0, r)) for _ in range(H)])
+    _check_forward_plan(B, Bsz, H, N, branches, offs if seed % 2 else None)
+
+
+def test_forward_plan_packs_the_row_groups_of_small_images(B):
+    """512^2 image (N = 1024) with the workload's branch family: the rows of one window of the narrowest branch fall
+    into groups of 128, 64 and 64 rows by which dilated branches also keep them; apart they are 12 part-filled
+    tiles per head walking 4, 6 and 8 steps (72 in all), packed they are 4 full tiles of 8 steps.  At 1024^2 every
+    group fills whole tiles and the plan is the plain one."""
+    wl = lambda N: [(N // 4, 1), (N // 2, 2), (N, 4)]
+    plain, packed = B.plan_describe(1, 12, 1024, wl(1024)), B.plan_describe_forward(1, 12, 1024, wl(1024))
+    assert len(plain["tiles"]) == 12 * 12 and int(plain["tiles"][:, 5].sum()) == 12 * 72
+    assert len(packed["tiles"]) == 12 * 4 and np.all(packed["tiles"][:, 2] == 256) and np.all(packed["tiles"][:, 5] == 8)
+    assert np.all(packed["rows"] >= 0)
+    # 256^2: groups of 32, 16 and 16 rows, one wave each with filler slots up to the next wave: 12 tiles of 1, 2 and
+    # 3 steps per head apart (24 steps), 4 tiles and 12 steps packed
+    plain, small = B.plan_describe(1, 6, 256, wl(256)), B.plan_describe_forward(1, 6, 256, wl(256))
+    assert len(plain["tiles"]) == 6 * 12 and int(plain["tiles"][:, 5].sum()) == 6 * 24
+    assert len(small["tiles"]) == 6 * 4 and int(small["tiles"][:, 5].sum()) == 6 * 12
+    assert int((small["rows"] < 0).sum()) > 0 and int((small["rows"] >= 0).sum()) == 6 * 256
+    plain, packed = B.plan_describe(1, 12, 4096, wl(4096)), B.plan_describe_forward(1, 12, 4096, wl(4096))
+    for key in ("tiles", "rows", "segs", "items"):
+        assert np.array_equal(plain[key], packed[key])
+    assert np.all(packed["wave_mult"] == packed["segs"][:, 3:4])
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys, os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))

@@ -130,6 +130,28 @@ def test_bf16_small_multi_tile(B, oracle):
     assert bool((out2 == out).all()) and bool((lse2 == lse).all())
 
 
+@pytest.mark.parametrize("Bsz,N,H,branches,split", [
+    (2, 256, 6, [(64, 1), (128, 2), (256, 4)], False),       # 256^2 image: groups of 32, 16, 16 rows, filler slots between them
+    (3, 1024, 12, [(256, 1), (512, 2), (1024, 4)], False),   # 512^2 image: groups of 128, 64, 64 rows fill a tile exactly
+    (1, 2048, 4, [(512, 1), (1024, 2), (2048, 4)], True),    # two groups of 128 rows share a tile whose walk is split over workgroups
+    (2, 600, 3, [(100, 1), (300, 2), (600, 3), (50, 1)], False),   # ragged groups, rates 2 and 3
+])
+def test_bf16_tiles_that_pack_several_row_groups(B, oracle, Bsz, N, H, branches, split):
+    """Row groups that fill only part of a tile share one (each on waves of its own, the tile walking the union of
+    their key lists, a wave masking the progressions its rows do not attend to): results as from the definition."""
+    plan = B.plan_describe_forward(Bsz, H, N, branches)
+    plain = B.plan_describe(Bsz, H, N, branches)
+    assert len(plan["tiles"]) < len(plain["tiles"]) and int((plan["wave_mult"] == 0).sum()) > 0
+    assert (B.workspace_bytes(Bsz, H, N, 64, B.DFA_BF16, branches) > 0) == split
+    (q, k, v), ex = make_qkv(110 + N, Bsz, N, H, 64, "bf16")
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
+    _check_bf16(out, lse, o_ref, l_ref, f"bf16 packed N={N}", rows=(oracle, ex, branches, 0.125, None))
+    if split:
+        out_u, lse_u = B.forward(q, k, v, branches, 0.125, workspace=None)      # the same tiles walked whole
+        _check_bf16(out_u, lse_u, o_ref, l_ref, f"bf16 packed unsplit N={N}", rows=(oracle, ex, branches, 0.125, None))
+
+
 def test_bf16_ragged_tiles_explicit_offsets_and_uncovered_rows(B, oracle):
     Bsz, N, H, D = 2, 1200, 3, 64
     branches = [(120, 3), (600, 2), (1200, 12)]
