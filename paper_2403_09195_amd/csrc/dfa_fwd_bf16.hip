@@ -91,8 +91,9 @@ __device__ __forceinline__ void issue_stage(const FwdParams& p, const uint16_t* 
 // If a lane's partial row sum of one 32-key block exceeds this, some exponent may have left
 // the comfortable range and the reference exponent is moved up (see rebase_block).
 constexpr float kRebaseThreshold = 256.0f;
-// Reference exponent before the first score of a row: far below any scaled score of finite inputs.
-constexpr float kRefStart = -1.0e30f;
+// Reference exponent before the first score of a row (kernel variant for packed tiles): below any scaled score
+// that fp32 holds with room to spare, and finite.
+constexpr float kRefStart = -3.0e38f;
 
 // Softmax numerators of one 32-key block against the current reference exponents m_ref (no
 // row maximum is taken here): p = exp2(c*s - m_ref), rounded to bf16 (nearest even) and packed
