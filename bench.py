@@ -157,16 +157,19 @@ def stage_report(binding, torch, q, k, v, branches, scale, steps, warmup):
             "note": "unfused_path_ms = the three unmerged branch launches + merge; the fused dfa_forward does all of it in one launch"}
 
 
-def sweep_report(binding, synth, torch, np, steps, warmup):
+def sweep_report(binding, synth, torch, np, steps, warmup, only=None):
     """Section 4.3's ablation (Fig. 4) as a synthetic sweep: image sizes 256^2, 512^2, 1024^2 (N = 256, 1024, 4096
     tokens of 16 x 16 patches), embed 384 (6 heads) and 768 (12 heads), B = 16.  For each shape: the three
     dilated branches scaled to it ((N/4, 1), (N/2, 2), (N, 4)) through dfa_forward; dense attention over all N
     tokens through dfa_forward (one branch with w = N, r = 1: "FlashAttention on"); and dense attention with the
-    score matrix held in memory (dfa_dense_unfused: "FlashAttention off")."""
+    score matrix held in memory (dfa_dense_unfused: "FlashAttention off").  only = (image side, heads): that row alone
+    (for a kernel trace of one shape)."""
     rows = []
     Bsz, D, scale = 16, 64, 0.125
     for H in (6, 12):
         for N in (256, 1024, 4096):
+            if only and (int(N ** 0.5) * 16, H) != tuple(only):
+                continue
             st, _ = synth.qkv(synth.BASE_SEED + 10 + H + N, Bsz, N, H, D, "bf16")
             q, k, v = (torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda() for a in st)
             out = torch.empty_like(q)
@@ -335,6 +338,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="input-size sweep of the paper's ablation (256^2, 512^2, 1024^2 images; 6 and 12 heads): "
                          "dilated attention against dense attention in the same kernel (w = N, r = 1)")
+    ap.add_argument("--sweep-only", type=int, nargs=2, metavar=("SIDE", "HEADS"), default=None,
+                    help="with --sweep: only the row of this image side (256, 512 or 1024) and head count (6 or 12)")
     ap.add_argument("--tile-cost", action="store_true",
                     help="single-branch launches of growing segment length on the throughput shape: cost per 64-key "
                          "step and per tile of the forward kernel")
@@ -382,7 +387,7 @@ def main():
                                       args.layers, args.heads)))
         return
     if args.sweep:
-        print(json.dumps(sweep_report(binding, synth, torch, np, args.steps, args.warmup)))
+        print(json.dumps(sweep_report(binding, synth, torch, np, args.steps, args.warmup, args.sweep_only)))
         return
     if args.tile_cost:
         print(json.dumps(tile_cost_report(binding, synth, torch, np)))
