@@ -43,7 +43,7 @@
  *     a plan is shared and never written after its upload.
  *   - Workspace.  A bf16 dfa_forward with fewer workgroups than the chip has room for (a single
  *     image, say) is faster when the long key walks are shared out over several workgroups
- *     whose fp32 partial results are merged afterwards.  Those partial results live in a workspace that the caller
+ *     whose partial results (out in bf16, lse in fp32) are merged afterwards.  Those partial results live in a workspace that the caller
  *     owns: dfa_workspace_bytes() says how much the shape needs (0 = none), and each call that
  *     may overlap another one needs a workspace of its own.  With workspace == NULL the call
  *     runs unsplit: same results to within rounding, slower for such shapes.
@@ -105,7 +105,7 @@ int dfa_index_map_device(int32_t N, int32_t H, dfa_branch_t br, const int32_t *h
 
 /*
  * Bytes of device workspace that dfa_forward / dfa_encoder_stack use for this shape on the current
- * device (section 3.1's operator has no such notion: this is the room for the fp32 partial results
+ * device (section 3.1's operator has no such notion: this is the room for the partial results
  * of a launch whose tiles are each walked by several workgroups, see "Workspace" above).  0 when the
  * shape needs none, for dt = DFA_F32, and for arguments dfa_forward would reject.  Host only: builds
  * the launch plan on the host, allocates nothing on the device; asks the current device for its

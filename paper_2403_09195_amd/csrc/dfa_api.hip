@@ -17,7 +17,7 @@
 #include "dfa_plan.h"
 
 // Scratch memory of dfa_forward_static, the entry point for callers that cannot allocate: the launch plan
-// of the shape last used on this device, followed by the fp32 partial results of a split launch.  One copy
+// of the shape last used on this device, followed by the partial results of a split launch.  One copy
 // per GPU, held until the process ends.  Host code never uses this name as an address: the device address
 // of each GPU's copy comes from hipGetSymbolAddress, taken in dfa_forward_static with that GPU current.
 constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
@@ -40,7 +40,7 @@ struct DevicePlan {
     int device = 0;
     size_t bytes = 0;
     // launches with few workgroups walk their tiles with n_split_wgs workgroups in all (see split_plan and
-    // launch_fwd_bf16_split) when the caller brings a workspace for their fp32 partial results; 0: never split
+    // launch_fwd_bf16_split) when the caller brings a workspace for their partial results; 0: never split
     const SplitWg* split_wgs = nullptr;
     const ItemParts* item_parts = nullptr;
     int32_t n_split_wgs = 0;
@@ -80,9 +80,9 @@ constexpr size_t kMaxCachedBytes = (size_t)256 << 20;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// fp32 partial results of a split launch: one block (a tile's rows of out, then of lse) per workgroup
+// partial results of a split launch: one block (a tile's rows of out in bf16, then of lse in fp32) per workgroup
 size_t split_bytes(int32_t n_split_wgs) {
-    return n_split_wgs > 0 ? align256((size_t)n_split_wgs * kSplitBlockFloats * sizeof(float)) : 0;
+    return n_split_wgs > 0 ? align256((size_t)n_split_wgs * kSplitBlockBytes) : 0;
 }
 
 // packed: the plan of the bf16 forward kernel (row groups may share a tile, multiplicities per wave); the fp32 and

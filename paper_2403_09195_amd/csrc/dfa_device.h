@@ -34,7 +34,7 @@ struct FwdParams {
     int32_t H, N;
     float scale;        // multiplies q.k
     // Split launches only (few workgroups, see launch_fwd_bf16_split): workgroup g walks the share of a tile's
-    // 64-key steps that split_wgs[g] names and leaves its fp32 partial result in block g of split_ws;
+    // 64-key steps that split_wgs[g] names and leaves its partial result in block g of split_ws;
     // launch_merge_split then writes out and lse.
     const SplitWg* split_wgs;
     const ItemParts* item_parts;

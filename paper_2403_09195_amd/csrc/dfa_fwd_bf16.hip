@@ -281,8 +281,9 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
     l_run[1] += psum[1];
 }
 
-// kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves an fp32
-// partial result (rows in tile order) in its own block of the workspace; OutT is float then.
+// kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves a partial
+// result (rows in tile order: out normalised and rounded to bf16 like a final one, lse in fp32) in its own block of
+// the workspace; OutT is bf16 then.
 // kPacked: the plan has tiles that pack several row groups (multiplicities per wave, filler slots); plans without
 // such tiles run the variant that has none of that in its way.
 template <typename OutT, bool kSplit, bool kPacked>
@@ -357,10 +358,11 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     float* const lse_out = p.lse;
     const int64_t out_bh = (int64_t)b * p.N * p.H + h;   // in rows; row n adds n * H
     // split launches: this workgroup's block of partial results, out [256][64] then lse [256], rows in tile order
-    float* const blk = kSplit ? p.split_ws + (int64_t)blockIdx.x * kSplitBlockFloats : nullptr;
+    char* const blk = kSplit ? reinterpret_cast<char*>(p.split_ws) + (int64_t)blockIdx.x * kSplitBlockBytes : nullptr;
+    float* const blk_lse = reinterpret_cast<float*>(blk + kTileRows * kD * 2);
 
     if (kSplit && tile.nseg == 0) {
-        blk[kTileRows * kD + tid] = -INFINITY;     // the merge writes the zero rows
+        blk_lse[tid] = -INFINITY;     // the merge writes the zero rows
         return;
     }
     if (tile.nseg == 0) {
@@ -421,7 +423,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const int first = part * n_steps / nparts, last = (part + 1) * n_steps / nparts;
         n_steps = last - first;
         if (n_steps == 0) {        // a tile with fewer steps than parts: this part has no keys
-            blk[kTileRows * kD + tid] = -INFINITY;
+            blk_lse[tid] = -INFINITY;
             return;
         }
         int skip = first;
@@ -575,7 +577,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         inv[qb] = 1.0f / l_tot;
         const float lse_row = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
         if (kSplit) {
-            if (g_e == 0) blk[kTileRows * kD + slot] = slot < tile.nrows ? lse_row : -INFINITY;
+            if (g_e == 0) blk_lse[slot] = slot < tile.nrows ? lse_row : -INFINITY;
         } else if (lse_out && g_e == 0 && slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
             lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = lse_row;
         }
@@ -605,7 +607,9 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             for (int s = 0; s < 8; ++s) {
                 const int row = 8 * s + srow, slot = wave * 64 + row;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
-                if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
+                if (kSplit) {
+                    if (slot < tile.nrows) *reinterpret_cast<u32x4*>(blk + slot * (kD * 2) + 16 * schunk) = val;
+                } else if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
                     const int64_t n = row_idx[slot];
                     *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(out + (out_bh + n * p.H) * kD) + 16 * schunk) = val;
                 }
@@ -615,9 +619,9 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int slot = wave * 64 + qb * 32 + j_e;
-            if (slot < tile.nrows && (kSplit || !kPacked || row_idx[slot] >= 0)) {
+            if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
                 const int64_t n = row_idx[slot];
-                OutT* op = kSplit ? reinterpret_cast<OutT*>(blk) + slot * kD : out + (out_bh + n * p.H) * kD;
+                OutT* op = out + (out_bh + n * p.H) * kD;
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -632,33 +636,35 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 
 // Merge of a split launch: combines the partial results of a launch item's shares by their log-sum-exp weights (the
 // same formula as the stand-alone branch merge: a share is attention over a part of the row's keys) and writes the
-// rows at their tokens.  Grid (items, 16): a workgroup takes sixteen rows of the tile, sixteen lanes to a row with
-// four features each; all loads go out before the first is used.
+// rows at their tokens.  Grid (items, 8): a workgroup takes 32 rows of the tile, eight lanes to a row with eight
+// features each.  The shares' blocks are addressed from the item's entry of item_parts alone, so their loads go out
+// together with that of the row's token (every block has all 256 rows, whatever the tile's count).
 __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
-    const Item item = p.items[blockIdx.x];
-    if (item.tile < 0) return;
-    const Tile tile = item.t;
-    const int r = blockIdx.y * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
-    if (r >= tile.nrows) return;
     const ItemParts ip = p.item_parts[blockIdx.x];
-    const float* blk0 = p.split_ws + (int64_t)ip.first_wg * kSplitBlockFloats;
-    const int32_t n = p.rows[tile.row_begin + r];
-    if (n < 0) return;                  // filler slot of a packed tile
+    const Item item = p.items[blockIdx.x];
+    if (ip.nparts == 0) return;         // padding item
+    const int r = blockIdx.y * 32 + (threadIdx.x >> 3), sub = threadIdx.x & 7;
+    const char* blk0 = reinterpret_cast<const char*>(p.split_ws) + (int64_t)ip.first_wg * kSplitBlockBytes;
     float lb[kMaxSplit];
-    float4 o[kMaxSplit];
+    bf16x8 o[kMaxSplit];
 #pragma unroll
     for (int x = 0; x < kMaxSplit; ++x) {
         lb[x] = -INFINITY;
-        o[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+        o[x] = bf16x8{};
         if (x < ip.nparts) {
-            lb[x] = blk0[(int64_t)x * kSplitBlockFloats + kTileRows * kD + r];
-            o[x] = *reinterpret_cast<const float4*>(blk0 + (int64_t)x * kSplitBlockFloats + r * kD + 4 * sub);
+            const char* b = blk0 + (int64_t)x * kSplitBlockBytes;
+            lb[x] = reinterpret_cast<const float*>(b + kTileRows * kD * 2)[r];
+            o[x] = *reinterpret_cast<const bf16x8*>(b + (r * kD + 8 * sub) * 2);
         }
     }
+    const Tile tile = item.t;
+    if (r >= tile.nrows) return;
+    const int32_t n = p.rows[tile.row_begin + r];
+    if (n < 0) return;                  // filler slot of a packed tile
     float m = -INFINITY;
 #pragma unroll
     for (int x = 0; x < kMaxSplit; ++x) m = fmaxf(m, lb[x]);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float L = -INFINITY;
     if (m > -INFINITY) {
         float w[kMaxSplit], z = 0.f;
@@ -673,14 +679,14 @@ __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
         for (int x = 0; x < kMaxSplit; ++x) {
             if (lb[x] == -INFINITY) continue;      // such a share has written no rows: its block holds anything
             const float ws = w[x] * inv;
-            acc.x = fmaf(ws, o[x].x, acc.x);
-            acc.y = fmaf(ws, o[x].y, acc.y);
-            acc.z = fmaf(ws, o[x].z, acc.z);
-            acc.w = fmaf(ws, o[x].w, acc.w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(ws, (float)o[x][e], acc[e]);
         }
     }
-    const bf16x4 ob = {(__bf16)acc.x, (__bf16)acc.y, (__bf16)acc.z, (__bf16)acc.w};
-    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.out) + (((int64_t)item.b * p.N + n) * p.H + tile.h) * kD + 4 * sub) = ob;
+    bf16x8 ob;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ob[e] = (__bf16)acc[e];
+    *reinterpret_cast<bf16x8*>(static_cast<__bf16*>(p.out) + (((int64_t)item.b * p.N + n) * p.H + tile.h) * kD + 8 * sub) = ob;
     if (p.lse && sub == 0) p.lse[((int64_t)item.b * p.H + tile.h) * p.N + n] = L;
 }
 
@@ -698,18 +704,18 @@ hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, bool p
 }
 
 // Launches with few workgroups are bound by the longest tile's walk, not by throughput: there the tiles are walked by
-// several workgroups each (p.split_wgs), every one over a share of the steps, into fp32 partial results (p.split_ws)
+// several workgroups each (p.split_wgs), every one over a share of the steps, into partial results (p.split_ws)
 // that launch_merge_split combines.
 hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, bool packed, hipStream_t st) {
     if (packed)
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
 hipError_t launch_merge_split(const FwdParams& p, int n_items, hipStream_t st) {
-    hipLaunchKernelGGL(merge_split_kernel, dim3(n_items, kTileRows / 16), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(merge_split_kernel, dim3(n_items, kTileRows / 32), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

@@ -54,8 +54,8 @@ struct ChipShape {
 };
 
 // Split launches (few workgroups, see split_plan): workgroup g of the launch walks share `part` of `nparts` of the
-// 64-key steps of launch item `item` and leaves its fp32 partial result in block g of the workspace
-// (kSplitBlockFloats floats: out [256 rows][64], then lse [256], rows in tile order).
+// 64-key steps of launch item `item` and leaves its partial result in block g of the workspace
+// (kSplitBlockBytes: out [256 rows][64] in bf16, then lse [256] in fp32, rows in tile order).
 struct SplitWg {
     int32_t item;
     int32_t part_nparts;    // part | nparts << 16
@@ -64,7 +64,7 @@ struct ItemParts {          // per launch item: its workgroups are first_wg .. f
     int32_t first_wg;
     int32_t nparts;
 };
-constexpr int kSplitBlockFloats = kTileRows * (DFA_HEAD_DIM + 1);
+constexpr int kSplitBlockBytes = kTileRows * (DFA_HEAD_DIM * 2 + 4);
 constexpr int kMaxSplit = 4;             // most shares a tile is cut into
 constexpr int kMinShareSteps = 8;        // a share of fewer 64-key steps is not worth a partial result and its merge
 

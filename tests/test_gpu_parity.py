@@ -152,6 +152,19 @@ def test_bf16_tiles_that_pack_several_row_groups(B, oracle, Bsz, N, H, branches,
         _check_bf16(out_u, lse_u, o_ref, l_ref, f"bf16 packed unsplit N={N}", rows=(oracle, ex, branches, 0.125, None))
 
 
+def test_bf16_packed_plan_of_many_workgroups(B, oracle):
+    """A long launch of packed tiles (several rounds of the chip's workgroup slots): 4096 (b, h) units of a 256^2
+    image, 16384 workgroups of three or four row groups each."""
+    Bsz, N, H = 128, 256, 32
+    branches = [(64, 1), (128, 2), (256, 4)]
+    plan = B.plan_describe_forward(Bsz, H, N, branches)
+    assert int((plan["items"][:, 0] >= 0).sum()) == 16384 and int((plan["wave_mult"] == 0).sum()) > 0
+    (q, k, v), ex = make_qkv(140, Bsz, N, H, 64, "bf16")
+    out, lse = B.forward(q, k, v, branches, 0.125)
+    o_ref, l_ref = oracle.forward(*ex, branches, 0.125)
+    _check_bf16(out, lse, o_ref, l_ref, "bf16 packed, long launch", rows=(oracle, ex, branches, 0.125, None))
+
+
 def test_bf16_ragged_tiles_explicit_offsets_and_uncovered_rows(B, oracle):
     Bsz, N, H, D = 2, 1200, 3, 64
     branches = [(120, 3), (600, 2), (1200, 12)]

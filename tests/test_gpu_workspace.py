@@ -1,4 +1,4 @@
-"""The caller-owned workspace of dfa_forward (room for the fp32 partial results of a launch whose tiles are
+"""The caller-owned workspace of dfa_forward (room for the partial results of a launch whose tiles are
 walked by several workgroups each): calls of one shape that overlap on two streams, each with a workspace of its
 own, give the results of serial calls; without a workspace the unsplit launch agrees to rounding; too small a
 workspace is refused.  All through the C ABI."""
@@ -27,7 +27,7 @@ def test_two_streams_one_shape_each_with_its_own_workspace(B, oracle):
     import torch
     Bsz, N, H, D = 1, 4096, 12, 64
     need = B.workspace_bytes(Bsz, H, N, D, B.DFA_BF16, SAM_BRANCHES)
-    assert need == 512 * 256 * 65 * 4                       # this shape is split: one block of partial results per workgroup slot
+    assert need == 512 * 256 * (64 * 2 + 4)                       # this shape is split: one block of partial results per workgroup slot
     inputs = [make_qkv(900 + i, Bsz, N, H, D, "bf16") for i in range(2)]
     serial = []
     for (q, k, v), _ in inputs:
