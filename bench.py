@@ -232,12 +232,12 @@ def tile_cost_report(binding, synth, torch, np):
             "note": "two workgroup slots share a CU; launch_us is the best HIP-event mean of three runs of 30 launches"}
 
 
-def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=12, H=12):
+def stack_report(binding, synth, torch, np, steps, warmup, cpu_baseline, layers=12, H=12, batch=None):
     """The encoder attention stack: 12 layers, embed 768 = 12 heads x 64, B = 8 images of 4096 tokens, bf16;
     per layer QKV projection (768 -> 2304), dilated attention, output projection (768 -> 768); weights
     N(0, 0.02^2), input N(0, 1), no bias, residual or normalisation.  One step = all 12 layers."""
     cfg = synth.CONFIGS["stack_layer"]
-    Bsz, N, D, branches = cfg["B"], cfg["N"], cfg["D"], cfg["branches"]
+    Bsz, N, D, branches = batch or cfg["B"], cfg["N"], cfg["D"], cfg["branches"]
     E, scale, seed = H * D, 1.0 / (D ** 0.5), cfg["seed"]
 
     def dev(bits):
@@ -350,6 +350,7 @@ def main():
                          "no operand bit flips): the gap to the synthetic-data time shows how far the launch is power-limited")
     ap.add_argument("--layers", type=int, default=12, help="--stack: number of layers")
     ap.add_argument("--heads", type=int, default=12, help="--stack: heads of 64 (embed = 64 * heads)")
+    ap.add_argument("--batch", type=int, default=None, help="--stack: images per step (default 8; 1 = the latency of one image)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of known size (FETCH_SIZE / WRITE_SIZE reference)")
     args = ap.parse_args()
@@ -384,7 +385,7 @@ def main():
 
     if args.stack:
         print(json.dumps(stack_report(binding, synth, torch, np, args.steps, args.warmup, not args.no_cpu_baseline,
-                                      args.layers, args.heads)))
+                                      args.layers, args.heads, args.batch)))
         return
     if args.sweep:
         print(json.dumps(sweep_report(binding, synth, torch, np, args.steps, args.warmup, args.sweep_only)))
