@@ -43,7 +43,7 @@
  *     a plan is shared and never written after its upload.
  *   - Workspace.  A bf16 dfa_forward with fewer workgroups than the chip has room for (a single
  *     image, say) is faster when the long key walks are shared out over several workgroups
- *     whose partial results (out in bf16, lse in fp32) are merged afterwards.  Those partial results live in a workspace that the caller
+ *     whose partial results (out in fp16 with a scale per row, lse in fp32) are merged afterwards.  Those partial results live in a workspace that the caller
  *     owns: dfa_workspace_bytes() says how much the shape needs (0 = none), and each call that
  *     may overlap another one needs a workspace of its own.  With workspace == NULL the call
  *     runs unsplit: same results to within rounding, slower for such shapes.
@@ -241,19 +241,20 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branc
  * The same view of the plan the bf16 dfa_forward launches.  It differs where row groups fill only part of a
  * 256-row tile (small images: the rows of one window of the narrowest branch fall into several groups by which
  * dilated branches also keep them): groups that share most of their keys are packed into one tile, each group
- * on 64-row waves of its own, and the tile walks the union of their key lists once.  A progression then has a
- * multiplicity per wave, 0 where that wave's rows do not attend to its keys (their scores are masked).
+ * on 32-row blocks of its own (half a wave: the unit with its own softmax state), and the tile walks the union of
+ * their key lists once.  A progression then has a multiplicity per block, 0 where that block's rows do not attend
+ * to its keys (their scores are masked).
  * Arguments as dfa_plan_describe, with
  *   rows       an entry < 0 is a filler slot between two groups of a packed tile (it holds ~n of a row n of the
  *              group before it; nothing is stored for it)
- *   segs       [n_segs][4] = (first key, key stride, key count, largest multiplicity over the waves)
- *   wave_mult  host int32 [n_segs][4]: multiplicity of the progression's keys for the rows of wave 0..3
- *              (slots 64w .. 64w+63 of the tile); NULL to skip
+ *   segs       [n_segs][4] = (first key, key stride, key count, largest multiplicity over the blocks)
+ *   block_mult host int32 [n_segs][8]: multiplicity of the progression's keys for the rows of block 0..7
+ *              (slots 32k .. 32k+31 of the tile); NULL to skip
  */
 int dfa_plan_describe_forward(int32_t B, int32_t H, int32_t N, const dfa_branch_t *branches, int32_t nb,
                               const int32_t *head_offsets, int32_t *n_tiles, int32_t *n_rows,
                               int32_t *n_segs, int32_t *n_items, int32_t *tiles, int32_t *rows,
-                              int32_t *segs, int32_t *wave_mult, int32_t *items);
+                              int32_t *segs, int32_t *block_mult, int32_t *items);
 
 /*
  * Projection either side of the operator inside an encoder layer (the ViT self-attention

@@ -444,7 +444,7 @@ def plan_describe(B, H, N, branches, head_offsets=None):
 
 def plan_describe_forward(B, H, N, branches, head_offsets=None):
     """Host view of the plan the bf16 forward launches (row groups packed into tiles): as plan_describe, plus
-    wave_mult [n_segs][4], the multiplicity of each progression for the rows of each wave of its tile."""
+    block_mult [n_segs][8], the multiplicity of each progression for the rows of each 32-row block of its tile."""
     import numpy as np
     br, nb = _branches(branches)
     off = _i32_array(head_offsets)
@@ -456,12 +456,12 @@ def plan_describe_forward(B, H, N, branches, head_offsets=None):
     tiles = np.zeros((nt, 6), dtype=np.int32)
     rows = np.zeros((nr,), dtype=np.int32)
     segs = np.zeros((max(ns, 1), 4), dtype=np.int32)
-    wave_mult = np.zeros((max(ns, 1), 4), dtype=np.int32)
+    block_mult = np.zeros((max(ns, 1), 8), dtype=np.int32)
     items = np.zeros((ni, 2), dtype=np.int32)
     p = lambda a: a.ctypes.data_as(_i32p)
-    _check(lib().dfa_plan_describe_forward(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(wave_mult), p(items)),
+    _check(lib().dfa_plan_describe_forward(B, H, N, br, nb, off, *refs, p(tiles), p(rows), p(segs), p(block_mult), p(items)),
            "dfa_plan_describe_forward")
-    return dict(tiles=tiles, rows=rows, segs=segs[:ns], wave_mult=wave_mult[:ns], items=items)
+    return dict(tiles=tiles, rows=rows, segs=segs[:ns], block_mult=block_mult[:ns], items=items)
 
 
 def release_plans():

@@ -34,8 +34,8 @@ struct DevicePlan {
     const int32_t* rows = nullptr;
     const KeySeg* segs = nullptr;
     const Item* items = nullptr;
-    const float* wave_mult = nullptr;   // plans of the bf16 forward only
-    bool packed_tiles = false;          // some tile packs several row groups: the kernel variant that reads wave_mult
+    const float* block_mult = nullptr;   // plans of the bf16 forward only
+    bool packed_tiles = false;          // some tile packs several row groups: the kernel variant that reads block_mult
     int32_t n_items = 0;
     int device = 0;
     size_t bytes = 0;
@@ -68,7 +68,7 @@ using PlanRef = std::shared_ptr<const DevicePlan>;
 // shares of a split launch, each part 256-byte aligned.
 struct PackedPlan {
     std::vector<char> bytes;
-    size_t off_segs = 0, off_items = 0, off_split_wgs = 0, off_item_parts = 0, off_wave_mult = 0;
+    size_t off_segs = 0, off_items = 0, off_split_wgs = 0, off_item_parts = 0, off_block_mult = 0;
     int32_t n_items = 0;
     int32_t n_split_wgs = 0;
     bool packed_tiles = false;
@@ -80,7 +80,7 @@ constexpr size_t kMaxCachedBytes = (size_t)256 << 20;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// partial results of a split launch: one block (a tile's rows of out in bf16, then of lse in fp32) per workgroup
+// partial results of a split launch: one block (a tile's rows of out in fp16, then their lse and scales in fp32) per workgroup
 size_t split_bytes(int32_t n_split_wgs) {
     return n_split_wgs > 0 ? align256((size_t)n_split_wgs * kSplitBlockBytes) : 0;
 }
@@ -98,17 +98,17 @@ int pack_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t n
     if (packed) split_plan(&hp, chip);
     const size_t b_wgs = align256(hp.split_wgs.size() * sizeof(SplitWg));
     const size_t b_parts = align256(hp.item_parts.size() * sizeof(ItemParts));
-    const size_t b_wmult = packed ? align256((hp.segs.size() + 1) * kTileWaves * sizeof(float)) : 0;
+    const size_t b_wmult = packed ? align256((hp.segs.size() + 1) * kTileBlocks * sizeof(float)) : 0;
     out->bytes.assign(b_rows + b_segs + b_items + b_wgs + b_parts + b_wmult, 0);
     out->off_segs = b_rows;
     out->off_items = b_rows + b_segs;
     out->off_split_wgs = out->off_items + b_items;
     out->off_item_parts = out->off_split_wgs + b_wgs;
-    out->off_wave_mult = out->off_item_parts + b_parts;
+    out->off_block_mult = out->off_item_parts + b_parts;
     if (packed) {
-        // log2 of the multiplicities, -inf where a wave's rows skip the progression
-        float* wm = reinterpret_cast<float*>(out->bytes.data() + out->off_wave_mult);
-        for (size_t x = 0; x < hp.wave_mult.size(); ++x) wm[x] = hp.wave_mult[x] > 0 ? std::log2((float)hp.wave_mult[x]) : -INFINITY;
+        // log2 of the multiplicities, -inf where a block's rows skip the progression
+        float* wm = reinterpret_cast<float*>(out->bytes.data() + out->off_block_mult);
+        for (size_t x = 0; x < hp.block_mult.size(); ++x) wm[x] = hp.block_mult[x] > 0 ? std::log2((float)hp.block_mult[x]) : -INFINITY;
     }
     if (!hp.rows.empty()) std::memcpy(out->bytes.data(), hp.rows.data(), hp.rows.size() * sizeof(int32_t));
     if (!hp.segs.empty()) std::memcpy(out->bytes.data() + b_rows, hp.segs.data(), hp.segs.size() * sizeof(KeySeg));
@@ -135,7 +135,7 @@ void point_plan(DevicePlan* dp, void* base, const PackedPlan& pp, int device) {
     dp->split_wgs = reinterpret_cast<const SplitWg*>(b + pp.off_split_wgs);
     dp->item_parts = reinterpret_cast<const ItemParts*>(b + pp.off_item_parts);
     dp->n_split_wgs = pp.n_split_wgs;
-    dp->wave_mult = reinterpret_cast<const float*>(b + pp.off_wave_mult);
+    dp->block_mult = reinterpret_cast<const float*>(b + pp.off_block_mult);
     dp->packed_tiles = pp.packed_tiles;
 }
 
@@ -322,7 +322,7 @@ int launch_forward(const DevicePlan& dp, const void* q, const void* k, const voi
     p.skb = sk.b; p.skn = sk.n; p.skh = sk.h;
     p.svb = sv.b; p.svn = sv.n; p.svh = sv.h;
     p.out = out; p.lse = lse;
-    p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items; p.wave_mult = dp.wave_mult;
+    p.rows = dp.rows; p.segs = dp.segs; p.items = dp.items; p.block_mult = dp.block_mult;
     p.H = H; p.N = N; p.scale = scale;
     p.split_wgs = dp.split_wgs; p.item_parts = dp.item_parts; p.split_ws = split_ws;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -655,7 +655,7 @@ namespace {
 
 int describe_plan(bool packed, int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
                   const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
-                  int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* wave_mult, int32_t* items) {
+                  int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* block_mult, int32_t* items) {
     if (!n_tiles || !n_rows || !n_segs || !n_items) return DFA_ERR_NULL;
     if (B <= 0) return DFA_ERR_SHAPE;
     const int rc = check_branches(H, N, branches, nb, head_offsets);
@@ -681,7 +681,7 @@ int describe_plan(bool packed, int32_t B, int32_t H, int32_t N, const dfa_branch
                 segs[4 * s + 2] = hp.segs[s].count;
                 segs[4 * s + 3] = hp.seg_mult[s];
             }
-        if (wave_mult) std::memcpy(wave_mult, hp.wave_mult.data(), hp.wave_mult.size() * sizeof(int32_t));
+        if (block_mult) std::memcpy(block_mult, hp.block_mult.data(), hp.block_mult.size() * sizeof(int32_t));
         if (items)
             for (size_t i = 0; i < hp.items.size(); ++i) {
                 items[2 * i] = hp.items[i].tile;
@@ -704,10 +704,10 @@ int dfa_plan_describe(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branc
 
 int dfa_plan_describe_forward(int32_t B, int32_t H, int32_t N, const dfa_branch_t* branches, int32_t nb,
                               const int32_t* head_offsets, int32_t* n_tiles, int32_t* n_rows, int32_t* n_segs,
-                              int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* wave_mult,
+                              int32_t* n_items, int32_t* tiles, int32_t* rows, int32_t* segs, int32_t* block_mult,
                               int32_t* items) {
     return describe_plan(true, B, H, N, branches, nb, head_offsets, n_tiles, n_rows, n_segs, n_items, tiles, rows, segs,
-                         wave_mult, items);
+                         block_mult, items);
 }
 
 int dfa_release_plans(void) {

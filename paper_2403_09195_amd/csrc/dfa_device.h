@@ -28,9 +28,9 @@ struct FwdParams {
     const int32_t* rows;
     const KeySeg* segs;
     const Item* items;
-    // bf16 kernel only: log2 of the multiplicity of each progression's keys for the rows of each of the tile's four
-    // waves, [segs][4]; -inf = the wave's rows do not attend to these keys (tiles that pack several row groups)
-    const float* wave_mult;
+    // bf16 kernel only: log2 of the multiplicity of each progression's keys for the rows of each of the tile's eight
+    // 32-row blocks, [segs][8]; -inf = the block's rows do not attend to these keys (tiles that pack several row groups)
+    const float* block_mult;
     int32_t H, N;
     float scale;        // multiplies q.k
     // Split launches only (few workgroups, see launch_fwd_bf16_split): workgroup g walks the share of a tile's

@@ -121,10 +121,13 @@ __device__ __forceinline__ void exp_block(const floatx16 (&s)[2], float c, const
 
 // Rare path of the online softmax: take the exact row maximum of this block, move the
 // reference exponent up to it, rescale the running sum and the accumulator.
+// kSkips: a query block may be skipping the progression in hand (m_ref = +inf, see the kernel): it stays as it is.
+template <bool kSkips>
 __device__ __forceinline__ void rebase_block(const floatx16 (&s)[2], float c, float (&m_ref)[2],
                                              float (&l_run)[2], floatx16 (&oacc)[2][2]) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+        if (kSkips && m_ref[qb] == INFINITY) continue;      // wave-uniform: a block skips as a whole
         float mx = s[qb][0];
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[qb][v]);
@@ -268,13 +271,14 @@ __device__ __forceinline__ void beat(const uint16_t* k_next, const uint16_t* v_p
 
 // The wave-uniform end of a beat: accept the numerators, or (rarely) move the reference
 // exponent and redo them.  oacc already holds every earlier block under the old reference.
+template <bool kSkips>
 __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur)[2][2], float c, float (&m_ref)[2],
                                        float (&l_run)[2], floatx16 (&oacc)[2][2], float (&psum)[2]) {
     // written so that NaN (-inf - -inf before the first rebase) trips the test
     const bool calm = psum[0] <= kRebaseThreshold && psum[1] <= kRebaseThreshold;
     if (__builtin_expect(__ballot(!calm) != 0ull, 0)) {
         // one rebase always suffices for finite inputs (every p of the block is <= 1 after it)
-        rebase_block(s_cur, c, m_ref, l_run, oacc);
+        rebase_block<kSkips>(s_cur, c, m_ref, l_run, oacc);
         exp_block(s_cur, c, m_ref, p_cur, psum);
     }
     l_run[0] += psum[0];
@@ -282,10 +286,10 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
 }
 
 // kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves a partial
-// result (rows in tile order: out normalised and rounded to bf16 like a final one, lse in fp32) in its own block of
-// the workspace; OutT is bf16 then.
-// kPacked: the plan has tiles that pack several row groups (multiplicities per wave, filler slots); plans without
-// such tiles run the variant that has none of that in its way.
+// result (rows in tile order: out normalised, divided by the row's largest magnitude and rounded to fp16; lse and
+// those row scales in fp32) in its own block of the workspace; OutT is not used then.
+// kPacked: the plan has tiles that pack several row groups (multiplicities per 32-row block, filler slots); plans
+// without such tiles run the variant that has none of that in its way.
 template <typename OutT, bool kSplit, bool kPacked>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void dfa_fwd_bf16_kernel(const FwdParams p) {
@@ -295,6 +299,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // the tile's key progressions, one copy per wave: log2_mult of wave w's copy is the figure for w's rows
     // (-inf: they do not attend to the progression's keys)
     __shared__ KeySeg seg_all[kPacked ? 4 : 1][kMaxTileSegs];
+    __shared__ float bias1_all[kPacked ? 4 : 1][kMaxTileSegs];   // kPacked: log2 m of the wave's second 32-row block
 
     int part = 0, nparts = 1, item_index = blockIdx.x;
     if (kSplit) {
@@ -324,12 +329,19 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         q_row[1] ^= q_row[1] >> 31;
     }
     KeySeg my_seg = p.segs[tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)];
-    float4 my_wmult = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (kPacked) my_wmult = *reinterpret_cast<const float4*>(p.wave_mult + 4 * (int64_t)(tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)));
+    float4 my_wmult = make_float4(0.f, 0.f, 0.f, 0.f), my_wmult2 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (kPacked) {
+        const float4* bm = reinterpret_cast<const float4*>(p.block_mult + 8 * (int64_t)(tile.seg_begin + min(tid, max(tile.nseg, 1) - 1)));
+        my_wmult = bm[0];
+        my_wmult2 = bm[1];
+    }
     // held here so that the compiler does not move these loads behind the Q loads (whose wait would then
     // sit in front of the barrier)
     asm volatile("" : "+v"(my_seg.key0), "+v"(my_seg.stride), "+v"(my_seg.count), "+v"(my_seg.log2_mult));
-    if (kPacked) asm volatile("" : "+v"(my_wmult.x), "+v"(my_wmult.y), "+v"(my_wmult.z), "+v"(my_wmult.w));
+    if (kPacked) {
+        asm volatile("" : "+v"(my_wmult.x), "+v"(my_wmult.y), "+v"(my_wmult.z), "+v"(my_wmult.w));
+        asm volatile("" : "+v"(my_wmult2.x), "+v"(my_wmult2.y), "+v"(my_wmult2.z), "+v"(my_wmult2.w));
+    }
     // Q fragments: B operand of S^T, lane (j, g) holds Q[row j][16*kk + 8*g .. +7]
     bf16x8 qf[2][4];
     {
@@ -343,10 +355,11 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     row_idx[tid] = my_row;
     if (tid < tile.nseg) {
         if constexpr (kPacked) {
-            my_seg.log2_mult = my_wmult.x; seg_all[0][tid] = my_seg;
-            my_seg.log2_mult = my_wmult.y; seg_all[1][tid] = my_seg;
-            my_seg.log2_mult = my_wmult.z; seg_all[2][tid] = my_seg;
-            my_seg.log2_mult = my_wmult.w; seg_all[3][tid] = my_seg;
+            // wave w holds blocks 2w and 2w + 1 of the tile
+            my_seg.log2_mult = my_wmult.x; seg_all[0][tid] = my_seg; bias1_all[0][tid] = my_wmult.y;
+            my_seg.log2_mult = my_wmult.z; seg_all[1][tid] = my_seg; bias1_all[1][tid] = my_wmult.w;
+            my_seg.log2_mult = my_wmult2.x; seg_all[2][tid] = my_seg; bias1_all[2][tid] = my_wmult2.y;
+            my_seg.log2_mult = my_wmult2.z; seg_all[3][tid] = my_seg; bias1_all[3][tid] = my_wmult2.w;
         } else {
             seg_all[0][tid] = my_seg;
         }
@@ -360,6 +373,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // split launches: this workgroup's block of partial results, out [256][64] then lse [256], rows in tile order
     char* const blk = kSplit ? reinterpret_cast<char*>(p.split_ws) + (int64_t)blockIdx.x * kSplitBlockBytes : nullptr;
     float* const blk_lse = reinterpret_cast<float*>(blk + kTileRows * kD * 2);
+    float* const blk_scale = blk_lse + kTileRows;
 
     if (kSplit && tile.nseg == 0) {
         blk_lse[tid] = -INFINITY;     // the merge writes the zero rows
@@ -479,6 +493,12 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     float m_ref[2] = {kPacked ? kRefStart : -INFINITY, kPacked ? kRefStart : -INFINITY};
     float l_run[2] = {0.f, 0.f};               // running sum of the row (the two lanes of a query hold the same value)
     float bias_cur = 0.f;                      // log2 m held in m_ref (wave-uniform)
+    // kPacked: the same per 32-row block of the wave, -inf while the block skips the progression in hand: m_ref is
+    // then +inf (every exponent -inf, every numerator an exact 0, no instruction spent on it) and the block's
+    // reference exponent waits in m_kept
+    float bias_q[2] = {0.f, 0.f};
+    float m_kept[2] = {kRefStart, kRefStart};
+    float bias1 = 0.f;                         // kPacked: log2 m of the progression in hand for the second block
 
     const bool wave_live = wave * 64 < tile.nrows;   // waves past the end of a short tile only help copying
 
@@ -509,21 +529,39 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     // a progression whose keys count m times for this wave's rows: log2 m comes off the reference exponents held
     // in m_ref; m = 0 (log2 m = -inf): the rows do not attend to these keys, every score of the step is masked
     auto enter_step = [&]() {
-        const bool attends = !kPacked || cur.bias > -INFINITY;
-        nvalid = attends ? min(kKeyTile, cur.count - cur.t * kKeyTile) : 0;
-        const float bias = attends ? cur.bias : bias_cur;
-        if (bias != bias_cur) {                // both blocks of this step still hold raw scores
-            m_ref[0] -= bias - bias_cur;
-            m_ref[1] -= bias - bias_cur;
-            bias_cur = bias;
+        nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+        if (cur.bias != bias_cur) {            // both blocks of this step still hold raw scores
+            m_ref[0] -= cur.bias - bias_cur;
+            m_ref[1] -= cur.bias - bias_cur;
+            bias_cur = cur.bias;
         }
     };
-    enter_step();
+    auto enter_step_packed = [&](bool first) {
+        nvalid = min(kKeyTile, cur.count - cur.t * kKeyTile);
+        // cur.bias (from the wave's copy of the list) is the first block's figure; the second block's is read when
+        // the walk enters a progression
+        if (first || cur.t == 0)
+            bias1 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bias1_all[wave][cur.s])));
+        const float now[2] = {cur.bias, bias1};
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            if (now[qb] != bias_q[qb]) {       // wave-uniform; both key blocks of this step still hold raw scores
+                const float ref = bias_q[qb] > -INFINITY ? m_ref[qb] + bias_q[qb] : m_kept[qb];
+                if (now[qb] > -INFINITY) {
+                    m_ref[qb] = ref - now[qb];
+                } else {
+                    m_kept[qb] = ref;
+                    m_ref[qb] = INFINITY;
+                }
+                bias_q[qb] = now[qb];
+            }
+    };
+    if constexpr (kPacked) enter_step_packed(true); else enter_step();
     if (wave_live) {
         scores_block(k_lds[0], fl, qf, s_a);
         if (nvalid < 32) mask_block(s_a, g, nvalid);
         beat<true, false>(k_lds[0] + 32 * kRowElems, v_lds[0], fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum, sel);
-        settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
+        settle<kPacked>(s_a, p_a, c, m_ref, l_run, oacc, psum);
     }
     for (int s = 0; s + 1 < n_steps; ++s) {
         const int stage_prev = stage == 0 ? kStages - 1 : stage - 1;
@@ -539,15 +577,15 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             // B(s): scores of block 2s+2, accumulation of block 2s, numerators of block 2s+1
             if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
             beat<true, true>(k_lds[stage_next], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum, sel);
-            settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
+            settle<kPacked>(s_b, p_b, c, m_ref, l_run, oacc, psum);
         }
         cursor_next(cur, seg_lds, tile.nseg);
-        enter_step();
+        if constexpr (kPacked) enter_step_packed(false); else enter_step();
         if (wave_live) {
             // A(s+1): scores of block 2s+3, accumulation of block 2s+1, numerators of block 2s+2
             if (nvalid < 32) mask_block(s_a, g, nvalid);
             beat<true, true>(k_lds[stage_next] + 32 * kRowElems, v_lds[stage] + 32 * kRowElems, fl, qf, s_a, s_b, p_b, p_a, oacc, c, m_ref, psum, sel);
-            settle(s_a, p_a, c, m_ref, l_run, oacc, psum);
+            settle<kPacked>(s_a, p_a, c, m_ref, l_run, oacc, psum);
         }
         stage = stage_next;
     }
@@ -555,7 +593,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         // B of the last step: accumulation of its first block, numerators of its second
         if (nvalid < 64) mask_block(s_b, g, nvalid - 32);
         beat<false, true>(k_lds[stage], v_lds[stage], fl, qf, s_b, s_a, p_a, p_b, oacc, c, m_ref, psum, sel);
-        settle(s_b, p_b, c, m_ref, l_run, oacc, psum);
+        settle<kPacked>(s_b, p_b, c, m_ref, l_run, oacc, psum);
     }
     // From here on the lane constants are worked out afresh, from a copy of the lane number the
     // compiler cannot see through: carried across the loop they would cost it registers that
@@ -575,14 +613,57 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         const int slot = wave * 64 + qb * 32 + j_e;
         const float l_tot = l_run[qb];
         inv[qb] = 1.0f / l_tot;
-        const float lse_row = (m_ref[qb] + bias_cur + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        const float ref = !kPacked ? m_ref[qb] + bias_cur : bias_q[qb] > -INFINITY ? m_ref[qb] + bias_q[qb] : m_kept[qb];
+        const float lse_row = (ref + __builtin_amdgcn_logf(l_tot)) * kLn2;
         if (kSplit) {
             if (g_e == 0) blk_lse[slot] = slot < tile.nrows ? lse_row : -INFINITY;
         } else if (lse_out && g_e == 0 && slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
             lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = lse_row;
         }
     }
-    if constexpr (sizeof(OutT) == 2) {
+    if constexpr (kSplit) {
+        // Partial rows leave as fp16, each divided by its largest magnitude (kept in fp32 beside the row's lse): half
+        // the bytes of fp32 rows, which is what a split launch is short of, at an error of 2^-12 of the row's largest
+        // value per element.  Same detour through LDS as for bf16 rows below: whole 128-byte lines.
+        typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+        float factor[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float mx = 0.f;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, fabsf(oacc[db][qb][v]));
+            mx = wave_half_max(mx) * inv[qb];            // the two lanes of a query hold the halves of its row
+            const float scale_row = mx > 0.f ? mx : 1.f;
+            factor[qb] = inv[qb] / scale_row;
+            const int slot = wave * 64 + qb * 32 + j_e;
+            if (g_e == 0) blk_scale[slot] = scale_row;
+        }
+        __syncthreads();           // every wave is done with the stages
+        constexpr int kPitch = kD * 2 + 16;
+        char* mine = reinterpret_cast<char*>(wave < 2 ? &k_lds[0][0] : &v_lds[0][0]) + (wave & 1) * (64 * kPitch);
+        if (wave_live) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const halfx4 o = {(_Float16)(oacc[db][qb][4 * vq] * factor[qb]), (_Float16)(oacc[db][qb][4 * vq + 1] * factor[qb]),
+                                          (_Float16)(oacc[db][qb][4 * vq + 2] * factor[qb]), (_Float16)(oacc[db][qb][4 * vq + 3] * factor[qb])};
+                        *reinterpret_cast<halfx4*>(mine + (32 * qb + j_e) * kPitch + (32 * db + 8 * vq + 4 * g_e) * 2) = o;
+                    }
+            // the wave reads back only what it wrote itself; LDS operations of a wave complete in order
+            const int srow = lane_e >> 3, schunk = lane_e & 7;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int row = 8 * s + srow, slot = wave * 64 + row;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
+                if (slot < tile.nrows) *reinterpret_cast<u32x4*>(blk + slot * (kD * 2) + 16 * schunk) = val;
+            }
+        }
+    } else if constexpr (sizeof(OutT) == 2) {
         // bf16 rows are 128 bytes.  A lane holds 4 consecutive d of one row per register quad; written
         // out directly that would be 8-byte pieces of 32 different lines per store.  Each wave
         // instead lays its 64 rows out row-major in a piece of the (now idle) K / V stages, at a
@@ -607,9 +688,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
             for (int s = 0; s < 8; ++s) {
                 const int row = 8 * s + srow, slot = wave * 64 + row;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(mine + row * kPitch + 16 * schunk);
-                if (kSplit) {
-                    if (slot < tile.nrows) *reinterpret_cast<u32x4*>(blk + slot * (kD * 2) + 16 * schunk) = val;
-                } else if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
+                if (slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
                     const int64_t n = row_idx[slot];
                     *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(out + (out_bh + n * p.H) * kD) + 16 * schunk) = val;
                 }
@@ -646,15 +725,19 @@ __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
     const int r = blockIdx.y * 32 + (threadIdx.x >> 3), sub = threadIdx.x & 7;
     const char* blk0 = reinterpret_cast<const char*>(p.split_ws) + (int64_t)ip.first_wg * kSplitBlockBytes;
     float lb[kMaxSplit];
-    bf16x8 o[kMaxSplit];
+    typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+    float sc[kMaxSplit];
+    halfx8 o[kMaxSplit];
 #pragma unroll
     for (int x = 0; x < kMaxSplit; ++x) {
         lb[x] = -INFINITY;
-        o[x] = bf16x8{};
+        sc[x] = 0.f;
+        o[x] = halfx8{};
         if (x < ip.nparts) {
             const char* b = blk0 + (int64_t)x * kSplitBlockBytes;
             lb[x] = reinterpret_cast<const float*>(b + kTileRows * kD * 2)[r];
-            o[x] = *reinterpret_cast<const bf16x8*>(b + (r * kD + 8 * sub) * 2);
+            sc[x] = reinterpret_cast<const float*>(b + kTileRows * kD * 2)[kTileRows + r];
+            o[x] = *reinterpret_cast<const halfx8*>(b + (r * kD + 8 * sub) * 2);
         }
     }
     const Tile tile = item.t;
@@ -678,7 +761,7 @@ __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
 #pragma unroll
         for (int x = 0; x < kMaxSplit; ++x) {
             if (lb[x] == -INFINITY) continue;      // such a share has written no rows: its block holds anything
-            const float ws = w[x] * inv;
+            const float ws = w[x] * inv * sc[x];
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] = fmaf(ws, (float)o[x][e], acc[e]);
         }
@@ -708,9 +791,9 @@ hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, bool p
 // that launch_merge_split combines.
 hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, bool packed, hipStream_t st) {
     if (packed)
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

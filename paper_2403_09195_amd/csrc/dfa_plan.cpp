@@ -16,9 +16,9 @@ int64_t steps_of(const std::vector<KeySeg>& segs) {
     return n;
 }
 
-// Multiplicities of one progression's keys for the (up to kTileWaves) row groups of a tile; 0 = the group's rows
+// Multiplicities of one progression's keys for the (up to kTileBlocks) row groups of a tile; 0 = the group's rows
 // do not attend to these keys.
-using MultVec = std::array<int32_t, kTileWaves>;
+using MultVec = std::array<int32_t, kTileBlocks>;
 
 // The multiset union of the progressions in `plain` rewritten as progressions in which every key has one
 // multiplicity.  A tile of one row group has one plain progression per member branch; a tile that packs several
@@ -115,7 +115,7 @@ struct RowGroup {
     std::vector<MultVec> list_mult;   // entry 0: the multiplicity of the progression's keys
 };
 
-int waves_of(const RowGroup& g) { return ((int)g.rows.size() + kWaveRows - 1) / kWaveRows; }
+int blocks_of(const RowGroup& g) { return ((int)g.rows.size() + kBlockRows - 1) / kBlockRows; }
 
 // Key list of a tile whose rows come from the groups in `pack` (group i of the pack = entry i of the
 // multiplicities): the coalesced union of their progressions where that saves steps, else the distinct
@@ -169,20 +169,20 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
     plan->rows.clear();
     plan->segs.clear();
     plan->seg_mult.clear();
-    plan->wave_mult.clear();
+    plan->block_mult.clear();
     plan->items.clear();
     plan->packed_tiles = false;
 
     std::vector<int64_t> tile_cost;   // (query, key) pairs of each tile
-    // appends a key list; wave_group[w] = which entry of a progression's multiplicities wave w's rows take (-1: none)
-    auto add_list = [&](const std::vector<KeySeg>& list, const std::vector<MultVec>& mult, const int (&wave_group)[kTileWaves]) {
+    // appends a key list; block_group[w] = which entry of a progression's multiplicities the rows of block w take (-1: none)
+    auto add_list = [&](const std::vector<KeySeg>& list, const std::vector<MultVec>& mult, const int (&block_group)[kTileBlocks]) {
         const int32_t seg_begin = (int32_t)plan->segs.size();
         plan->segs.insert(plan->segs.end(), list.begin(), list.end());
         for (const MultVec& m : mult) {
             int32_t most = 0;
-            for (int w = 0; w < kTileWaves; ++w) {
-                const int32_t mw = wave_group[w] < 0 ? 0 : m[wave_group[w]];
-                plan->wave_mult.push_back(mw);
+            for (int w = 0; w < kTileBlocks; ++w) {
+                const int32_t mw = block_group[w] < 0 ? 0 : m[block_group[w]];
+                plan->block_mult.push_back(mw);
                 most = std::max(most, mw);
             }
             plan->seg_mult.push_back(most);
@@ -223,7 +223,8 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
 
         // Row groups that fill only part of a tile.  Where such groups attend to many of the same keys (rows of one
         // window of a narrow branch that differ in which wider, dilated branches also keep them), a tile takes
-        // several of them, each in waves of its own: the tile walks the union of their lists once, and a wave whose
+        // several of them, each in 32-row blocks of its own (half a wave: the unit that has its own softmax state in the
+        // kernel): the tile walks the union of their lists once, and a block whose
         // rows do not attend to a progression masks its scores (multiplicity 0).  A group joins a tile when at least
         // half the steps of the shorter of the two lists are saved.
         const size_t G = groups.size();
@@ -232,19 +233,19 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             if (done[i]) continue;
             done[i] = 1;
             const RowGroup& g = *groups[i];
-            const bool small = pack && !g.plain.empty() && waves_of(g) < kTileWaves;
+            const bool small = pack && !g.plain.empty() && blocks_of(g) < kTileBlocks;
             std::vector<const RowGroup*> members = {&g};
             std::vector<KeySeg> list = g.list;
             std::vector<MultVec> list_mult = g.list_mult;
-            int waves = waves_of(g);
-            while (small && waves < kTileWaves) {
+            int blocks = blocks_of(g);
+            while (small && blocks < kTileBlocks) {
                 int64_t best = -1, best_saved = 0;
                 std::vector<KeySeg> best_list;
                 std::vector<MultVec> best_mult;
                 const int64_t have = steps_of(list);
                 for (size_t j = i + 1; j < std::min(G, i + 1 + kPackWindow); ++j) {
                     const RowGroup& c = *groups[j];
-                    if (done[j] || c.plain.empty() || waves + waves_of(c) > kTileWaves) continue;
+                    if (done[j] || c.plain.empty() || blocks + blocks_of(c) > kTileBlocks) continue;
                     std::vector<const RowGroup*> trial = members;
                     trial.push_back(&c);
                     std::vector<KeySeg> tl;
@@ -260,15 +261,15 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 if (best < 0) break;
                 done[best] = 1;
                 members.push_back(groups[best]);
-                waves += waves_of(*groups[best]);
+                blocks += blocks_of(*groups[best]);
                 list.swap(best_list);
                 list_mult.swap(best_mult);
             }
             const int32_t nseg = (int32_t)list.size();
             if (members.size() == 1) {
-                // tiles of one group: cut its rows into tiles that share the list; every wave takes entry 0
-                const int wave_group[kTileWaves] = {0, 0, 0, 0};
-                const int32_t seg_begin = add_list(list, list_mult, wave_group);
+                // tiles of one group: cut its rows into tiles that share the list; every block takes entry 0
+                const int block_group[kTileBlocks] = {0, 0, 0, 0, 0, 0, 0, 0};
+                const int32_t seg_begin = add_list(list, list_mult, block_group);
                 int64_t keys = 0;
                 for (const KeySeg& sg : list) keys += sg.count;
                 for (size_t lo = 0; lo < g.rows.size(); lo += kTileRows) {
@@ -280,10 +281,10 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 }
                 continue;
             }
-            // one tile of several groups: each starts on a wave of its own; the slots between the end of a group and
-            // the next wave hold ~row of the group's last row (a valid row to load, never stored)
+            // one tile of several groups: each starts on a block of its own; the slots between the end of a group and
+            // the next block hold ~row of the group's last row (a valid row to load, never stored)
             plan->packed_tiles = true;
-            int wave_group[kTileWaves] = {-1, -1, -1, -1};
+            int block_group[kTileBlocks] = {-1, -1, -1, -1, -1, -1, -1, -1};
             const int32_t row_begin = (int32_t)plan->rows.size();
             int w0 = 0;
             int64_t pairs = 0;
@@ -291,15 +292,15 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 const RowGroup& m = *members[gi];
                 if (gi > 0) {
                     const int32_t filler = ~members[gi - 1]->rows.back();
-                    while ((int32_t)plan->rows.size() - row_begin < w0 * kWaveRows) plan->rows.push_back(filler);
+                    while ((int32_t)plan->rows.size() - row_begin < w0 * kBlockRows) plan->rows.push_back(filler);
                 }
                 plan->rows.insert(plan->rows.end(), m.rows.begin(), m.rows.end());
-                for (int w = 0; w < waves_of(m); ++w) wave_group[w0 + w] = (int)gi;
-                w0 += waves_of(m);
+                for (int w = 0; w < blocks_of(m); ++w) block_group[w0 + w] = (int)gi;
+                w0 += blocks_of(m);
                 for (size_t x = 0; x < list.size(); ++x)
                     pairs += (int64_t)list[x].count * (list_mult[x][gi] ? 1 : 0) * (int64_t)m.rows.size();
             }
-            const int32_t seg_begin = add_list(list, list_mult, wave_group);
+            const int32_t seg_begin = add_list(list, list_mult, block_group);
             plan->tiles.push_back(Tile{h, row_begin, (int32_t)plan->rows.size() - row_begin, seg_begin, nseg, (int32_t)steps_of(list)});
             tile_cost.push_back(pairs);
         }

@@ -13,8 +13,8 @@
 namespace dfa {
 
 constexpr int kTileRows = 256;   // query rows per workgroup (4 waves x 64 rows)
-constexpr int kTileWaves = 4;
-constexpr int kWaveRows = 64;
+constexpr int kTileBlocks = 8;   // a wave's 64 rows are two blocks of 32, each with its own softmax state
+constexpr int kBlockRows = 32;
 constexpr int kPackWindow = 32;  // row groups (in signature order) after a group that are tried as its tile mates
 constexpr int kFwdWorkgroupsPerCu = 2;   // workgroups of the bf16 forward kernel that fit one compute unit
 constexpr int kTailItemsPerDie = 96;     // launch order: items at the end of a die's list that go heaviest first
@@ -55,7 +55,8 @@ struct ChipShape {
 
 // Split launches (few workgroups, see split_plan): workgroup g of the launch walks share `part` of `nparts` of the
 // 64-key steps of launch item `item` and leaves its partial result in block g of the workspace
-// (kSplitBlockBytes: out [256 rows][64] in bf16, then lse [256] in fp32, rows in tile order).
+// (kSplitBlockBytes: out [256 rows][64] in fp16, each row divided by its largest magnitude, then lse [256] and
+// those row scales [256] in fp32; rows in tile order).
 struct SplitWg {
     int32_t item;
     int32_t part_nparts;    // part | nparts << 16
@@ -64,19 +65,19 @@ struct ItemParts {          // per launch item: its workgroups are first_wg .. f
     int32_t first_wg;
     int32_t nparts;
 };
-constexpr int kSplitBlockBytes = kTileRows * (DFA_HEAD_DIM * 2 + 4);
+constexpr int kSplitBlockBytes = kTileRows * (DFA_HEAD_DIM * 2 + 8);
 constexpr int kMaxSplit = 4;             // most shares a tile is cut into
 constexpr int kMinShareSteps = 8;        // a share of fewer 64-key steps is not worth a partial result and its merge
 
 struct HostPlan {
     std::vector<Tile> tiles;
-    // token positions, tile after tile.  A tile that packs several row groups starts each group on a wave of its
-    // own; the slots in between hold ~n of a row n of the group (valid to load, never stored).
+    // token positions, tile after tile.  A tile that packs several row groups starts each group on a 32-row block of
+    // its own; the slots in between hold ~n of a row n of the group (valid to load, never stored).
     std::vector<int32_t> rows;
     std::vector<KeySeg> segs;
-    std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs (packed tiles: the largest of its waves)
-    std::vector<int32_t> wave_mult;  // [segs][kTileWaves]: multiplicity for the rows of each wave, 0 = they skip the keys
-    bool packed_tiles = false;       // some tile packs several row groups (wave_mult differs between waves, filler slots)
+    std::vector<int32_t> seg_mult;   // multiplicity of each entry of segs (packed tiles: the largest of its blocks)
+    std::vector<int32_t> block_mult; // [segs][kTileBlocks]: multiplicity for the rows of each 32-row block, 0 = they skip the keys
+    bool packed_tiles = false;       // some tile packs several row groups (block_mult differs between blocks, filler slots)
     std::vector<Item> items;
     std::vector<SplitWg> split_wgs;      // empty: the launch is not split
     std::vector<ItemParts> item_parts;
@@ -92,8 +93,8 @@ inline int32_t head_offset(const int32_t* offsets, int32_t H, int32_t x, int32_t
 
 // Builds tiles, row lists, key segments and the launch order for B images.
 // order_mode: 3 = default (see dfa_plan.cpp), 0 to 2 are alternatives kept for measurement.
-// pack: row groups of fewer than four waves may share a tile (only the bf16 forward kernel reads such tiles:
-// it takes its multiplicities per wave from wave_mult).
+// pack: row groups of fewer than eight 32-row blocks may share a tile (only the bf16 forward kernel reads such
+// tiles: it takes its multiplicities per block from block_mult).
 void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t nb,
                 const int32_t* offsets, int order_mode, const ChipShape& chip, bool pack, HostPlan* plan);
 

@@ -79,12 +79,12 @@ def test_forward_rejects_bad_arguments_before_any_gpu_work(B):
 
 
 def test_workspace_bytes_follows_the_split_rule(B):
-    """Room for the partial results of a split launch, one block of 256 rows (out in bf16, then lse in fp32) per workgroup:
+    """Room for the partial results of a split launch, one block of 256 rows (out in fp16, then lse and a row scale in fp32) per workgroup:
     the single-image workload has 192 tiles of 16, 24 or 32 steps for 512 workgroup slots, and the longest walks
     are shared out until every slot has a workgroup; the batch of 16 fills the chip and needs none.  (Without a
     device the library assumes the MI355X's 256 compute units.)"""
     wl = [(1024, 1), (2048, 2), (4096, 4)]
-    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, wl) == 512 * 256 * (64 * 2 + 4)
+    assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_BF16, wl) == 512 * 256 * (64 * 2 + 8)
     assert B.workspace_bytes(16, 12, 4096, 64, B.DFA_BF16, wl) == 0
     assert B.workspace_bytes(1, 12, 4096, 64, B.DFA_F32, wl) == 0
     assert B.workspace_bytes(1, 12, 4096, 128, B.DFA_BF16, wl) == 0          # D the library does not take
@@ -314,10 +314,10 @@ def test_plan_of_random_problems(B, seed):
 
 def _check_forward_plan(B, Bsz, H, N, branches, offs, sample=None):
     """The plan of the bf16 forward: every (h, n) is stored by exactly one slot, and for every slot (filler slots
-    included: they are computed like the row they repeat) the progressions its wave takes, with the wave's
+    included: they are computed like the row they repeat) the progressions its 32-row block takes, with the block's
     multiplicities, add up to exactly the multiset of keys the definition gives the row."""
     p = B.plan_describe_forward(Bsz, H, N, branches, offs)
-    tiles, rows, segs, wm, items = p["tiles"], p["rows"], p["segs"], p["wave_mult"], p["items"]
+    tiles, rows, segs, wm, items = p["tiles"], p["rows"], p["segs"], p["block_mult"], p["items"]
     seen = np.zeros((H, N), dtype=np.int32)
     for (h, rb, nr, sb, ns, steps) in tiles:
         assert 1 <= nr <= 256 and ns <= 32
@@ -327,15 +327,15 @@ def _check_forward_plan(B, Bsz, H, N, branches, offs, sample=None):
         real = tile_rows[tile_rows >= 0]
         seen[h, real] += 1
         if ns:
-            live = wm[sb:sb + ns, :(nr + 63) // 64]
-            assert live.max(axis=0).min() >= 1 and live.max(axis=1).min() >= 1    # no idle wave, no unused progression
+            live = wm[sb:sb + ns, :(nr + 31) // 32]
+            assert live.max(axis=0).min() >= 1 and live.max(axis=1).min() >= 1    # no idle block, no unused progression
             assert np.array_equal(segs[sb:sb + ns, 3], wm[sb:sb + ns].max(axis=1))
-            assert np.all(wm[sb:sb + ns, (nr + 63) // 64:] == 0) or np.all(tile_rows >= 0)
+            assert np.all(wm[sb:sb + ns, (nr + 31) // 32:] == 0) or np.all(tile_rows >= 0)
         slots = range(nr) if sample is None else sample(nr)
         for slot in slots:
             n = int(tile_rows[slot])
             n = ~n if n < 0 else n
-            w = slot // 64
+            w = slot // 32
             got = [(int(segs[s][0]), int(segs[s][1]), int(segs[s][2]), int(wm[s][w])) for s in range(sb, sb + ns) if wm[s][w] > 0]
             counts, _ = _expected_multiset(N, h, n, branches, offs)
             mine = np.zeros(N, dtype=np.int32)
@@ -380,23 +380,24 @@ def test_forward_plan_of_random_problems(B, seed):
 def test_forward_plan_packs_the_row_groups_of_small_images(B):
     """512^2 image (N = 1024) with the workload's branch family: the rows of one window of the narrowest branch fall
     into groups of 128, 64 and 64 rows by which dilated branches also keep them; apart they are 12 part-filled
-    tiles per head walking 4, 6 and 8 steps (72 in all), packed they are 4 full tiles of 8 steps.  At 1024^2 every
+    tiles per head walking 4, 6 and 8 steps (72 in all), packed they are 4 full tiles of 8 steps (a group takes
+    whole 32-row blocks of a tile, two to a wave).  At 1024^2 every
     group fills whole tiles and the plan is the plain one."""
     wl = lambda N: [(N // 4, 1), (N // 2, 2), (N, 4)]
     plain, packed = B.plan_describe(1, 12, 1024, wl(1024)), B.plan_describe_forward(1, 12, 1024, wl(1024))
     assert len(plain["tiles"]) == 12 * 12 and int(plain["tiles"][:, 5].sum()) == 12 * 72
     assert len(packed["tiles"]) == 12 * 4 and np.all(packed["tiles"][:, 2] == 256) and np.all(packed["tiles"][:, 5] == 8)
     assert np.all(packed["rows"] >= 0)
-    # 256^2: groups of 32, 16 and 16 rows, one wave each with filler slots up to the next wave: 12 tiles of 1, 2 and
-    # 3 steps per head apart (24 steps), 4 tiles and 12 steps packed
+    # 256^2: groups of 32, 16 and 16 rows, one 32-row block each (filler slots up to the next block): 12 tiles of 1, 2
+    # and 3 steps per head apart (24 steps), 2 tiles of six blocks and 4 steps packed
     plain, small = B.plan_describe(1, 6, 256, wl(256)), B.plan_describe_forward(1, 6, 256, wl(256))
     assert len(plain["tiles"]) == 6 * 12 and int(plain["tiles"][:, 5].sum()) == 6 * 24
-    assert len(small["tiles"]) == 6 * 4 and int(small["tiles"][:, 5].sum()) == 6 * 12
+    assert len(small["tiles"]) == 6 * 2 and np.all(small["tiles"][:, 2] == 192) and np.all(small["tiles"][:, 5] == 4)
     assert int((small["rows"] < 0).sum()) > 0 and int((small["rows"] >= 0).sum()) == 6 * 256
     plain, packed = B.plan_describe(1, 12, 4096, wl(4096)), B.plan_describe_forward(1, 12, 4096, wl(4096))
     for key in ("tiles", "rows", "segs", "items"):
         assert np.array_equal(plain[key], packed[key])
-    assert np.all(packed["wave_mult"] == packed["segs"][:, 3:4])
+    assert np.all(packed["block_mult"] == packed["segs"][:, 3:4])
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -141,7 +141,7 @@ def test_bf16_tiles_that_pack_several_row_groups(B, oracle, Bsz, N, H, branches,
     their key lists, a wave masking the progressions its rows do not attend to): results as from the definition."""
     plan = B.plan_describe_forward(Bsz, H, N, branches)
     plain = B.plan_describe(Bsz, H, N, branches)
-    assert len(plan["tiles"]) < len(plain["tiles"]) and int((plan["wave_mult"] == 0).sum()) > 0
+    assert len(plan["tiles"]) < len(plain["tiles"]) and int((plan["block_mult"] == 0).sum()) > 0
     assert (B.workspace_bytes(Bsz, H, N, 64, B.DFA_BF16, branches) > 0) == split
     (q, k, v), ex = make_qkv(110 + N, Bsz, N, H, 64, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125)
@@ -154,11 +154,11 @@ def test_bf16_tiles_that_pack_several_row_groups(B, oracle, Bsz, N, H, branches,
 
 def test_bf16_packed_plan_of_many_workgroups(B, oracle):
     """A long launch of packed tiles (several rounds of the chip's workgroup slots): 4096 (b, h) units of a 256^2
-    image, 16384 workgroups of three or four row groups each."""
+    image, 8192 workgroups of six row groups each."""
     Bsz, N, H = 128, 256, 32
     branches = [(64, 1), (128, 2), (256, 4)]
     plan = B.plan_describe_forward(Bsz, H, N, branches)
-    assert int((plan["items"][:, 0] >= 0).sum()) == 16384 and int((plan["wave_mult"] == 0).sum()) > 0
+    assert int((plan["items"][:, 0] >= 0).sum()) == 8192 and int((plan["block_mult"] == 0).sum()) > 0
     (q, k, v), ex = make_qkv(140, Bsz, N, H, 64, "bf16")
     out, lse = B.forward(q, k, v, branches, 0.125)
     o_ref, l_ref = oracle.forward(*ex, branches, 0.125)

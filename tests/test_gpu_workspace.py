@@ -27,7 +27,7 @@ def test_two_streams_one_shape_each_with_its_own_workspace(B, oracle):
     import torch
     Bsz, N, H, D = 1, 4096, 12, 64
     need = B.workspace_bytes(Bsz, H, N, D, B.DFA_BF16, SAM_BRANCHES)
-    assert need == 512 * 256 * (64 * 2 + 4)                       # this shape is split: one block of partial results per workgroup slot
+    assert need == 512 * 256 * (64 * 2 + 8)                       # this shape is split: one block of partial results per workgroup slot
     inputs = [make_qkv(900 + i, Bsz, N, H, D, "bf16") for i in range(2)]
     serial = []
     for (q, k, v), _ in inputs:
