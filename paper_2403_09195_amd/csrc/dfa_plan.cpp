@@ -113,6 +113,7 @@ struct RowGroup {
     std::vector<int64_t> plain_id;    // which (branch, part) each one is
     std::vector<KeySeg> list;         // what a tile of these rows alone walks
     std::vector<MultVec> list_mult;   // entry 0: the multiplicity of the progression's keys
+    int64_t key_lo = 0, key_hi = -1;  // first and last key of its progressions
 };
 
 int blocks_of(const RowGroup& g) { return ((int)g.rows.size() + kBlockRows - 1) / kBlockRows; }
@@ -189,7 +190,23 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
         }
         return seg_begin;
     };
+    // heads with the same start offsets in every branch have the same rows, lists and tiles: the later one's tiles
+    // are copies of the earlier one's (pointing at the same rows and progressions) under its own head number
+    std::map<std::vector<int32_t>, std::pair<size_t, size_t>> tiles_of_offsets;
     for (int32_t h = 0; h < H; ++h) {
+        std::vector<int32_t> head_key(nb);
+        for (int x = 0; x < nb; ++x) head_key[x] = head_offset(offsets, H, x, h, br[x].r);
+        const auto twin = tiles_of_offsets.find(head_key);
+        if (twin != tiles_of_offsets.end()) {
+            for (size_t t = twin->second.first; t < twin->second.second; ++t) {
+                Tile copy = plan->tiles[t];
+                copy.h = h;
+                plan->tiles.push_back(copy);
+                tile_cost.push_back(tile_cost[t]);
+            }
+            continue;
+        }
+        const size_t first_tile = plan->tiles.size();
         // signature of a row: for each branch the part that keeps it, or -1
         std::map<std::vector<int32_t>, RowGroup> by_sig;
         std::vector<int32_t> sig(nb);
@@ -215,6 +232,14 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 const int32_t count = (int32_t)((end - 1 - first) / br[x].r + 1);   // >= 1: a row of the part is kept
                 g.plain.push_back(KeySeg{(int32_t)first, br[x].r, count, 0.f});
                 g.plain_id.push_back((int64_t)x * ((int64_t)N + 1) + s[x]);
+                const int64_t last_key = first + (int64_t)(count - 1) * br[x].r;
+                if (g.key_hi < g.key_lo) {
+                    g.key_lo = first;
+                    g.key_hi = last_key;
+                } else {
+                    g.key_lo = std::min(g.key_lo, first);
+                    g.key_hi = std::max(g.key_hi, last_key);
+                }
             }
             // keys that several member branches keep are visited once, weighted by how many keep them
             if (!g.plain.empty()) tile_list({&g}, &g.list, &g.list_mult);
@@ -238,6 +263,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             std::vector<KeySeg> list = g.list;
             std::vector<MultVec> list_mult = g.list_mult;
             int blocks = blocks_of(g);
+            int64_t key_lo = g.key_lo, key_hi = g.key_hi;
             while (small && blocks < kTileBlocks) {
                 int64_t best = -1, best_saved = 0;
                 std::vector<KeySeg> best_list;
@@ -246,6 +272,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 for (size_t j = i + 1; j < std::min(G, i + 1 + kPackWindow); ++j) {
                     const RowGroup& c = *groups[j];
                     if (done[j] || c.plain.empty() || blocks + blocks_of(c) > kTileBlocks) continue;
+                    if (c.key_hi < key_lo || key_hi < c.key_lo) continue;      // no key in common: nothing to save
                     std::vector<const RowGroup*> trial = members;
                     trial.push_back(&c);
                     std::vector<KeySeg> tl;
@@ -262,6 +289,8 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
                 done[best] = 1;
                 members.push_back(groups[best]);
                 blocks += blocks_of(*groups[best]);
+                key_lo = std::min(key_lo, groups[best]->key_lo);
+                key_hi = std::max(key_hi, groups[best]->key_hi);
                 list.swap(best_list);
                 list_mult.swap(best_mult);
             }
@@ -304,6 +333,7 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
             plan->tiles.push_back(Tile{h, row_begin, (int32_t)plan->rows.size() - row_begin, seg_begin, nseg, (int32_t)steps_of(list)});
             tile_cost.push_back(pairs);
         }
+        tiles_of_offsets[head_key] = {first_tile, plan->tiles.size()};
     }
 
     // Launch order.  Workgroup i runs on die i mod 8, each die has its own L2, and the tiles

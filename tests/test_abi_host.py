@@ -393,7 +393,9 @@ def test_forward_plan_packs_the_row_groups_of_small_images(B):
     plain, small = B.plan_describe(1, 6, 256, wl(256)), B.plan_describe_forward(1, 6, 256, wl(256))
     assert len(plain["tiles"]) == 6 * 12 and int(plain["tiles"][:, 5].sum()) == 6 * 24
     assert len(small["tiles"]) == 6 * 2 and np.all(small["tiles"][:, 2] == 192) and np.all(small["tiles"][:, 5] == 4)
-    assert int((small["rows"] < 0).sum()) > 0 and int((small["rows"] >= 0).sum()) == 6 * 256
+    # heads 4 and 5 start at the offsets of heads 0 and 1 (h mod 1, 2, 4): their tiles point at the same rows and lists
+    assert int((small["rows"] < 0).sum()) > 0 and int((small["rows"] >= 0).sum()) == 4 * 256
+    assert np.array_equal(small["tiles"][8:, 1:], small["tiles"][:4, 1:]) and list(small["tiles"][8:, 0]) == [4, 4, 5, 5]
     plain, packed = B.plan_describe(1, 12, 4096, wl(4096)), B.plan_describe_forward(1, 12, 4096, wl(4096))
     for key in ("tiles", "rows", "segs", "items"):
         assert np.array_equal(plain[key], packed[key])
