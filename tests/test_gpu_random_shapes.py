@@ -111,6 +111,41 @@ def test_random_problem_with_many_branches_forward(B, oracle, seed):
         assert np.all(to_f64(out)[np.isneginf(l_ref).transpose(0, 2, 1)] == 0.0)
 
 
+def _small_group_problem(seed):
+    """Problems whose row groups are smaller than a tile and share keys: the workloads' nested family scaled to small
+    images, and sets of narrow windows with arbitrary rates and offsets."""
+    rng = np.random.default_rng(9000 + seed)
+    Bsz, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    if seed % 2 == 0:
+        N = int(rng.choice([128, 256, 384, 512, 768, 1024, 1536, 2048]))
+        nb = int(rng.integers(2, 5))
+        branches = [(max(N >> (nb - 1 - x), 1 << x), 1 << x) for x in range(nb)]
+        return Bsz, N, H, branches, None
+    N = int(rng.integers(64, 1500))
+    branches = [(int(rng.choice([16, 32, 48, 64, 100, 128, 200, 256])), int(rng.integers(1, 5))) for _ in range(int(rng.integers(2, 6)))]
+    offs = [[int(rng.integers(0, r)) for _ in range(H)] for (_, r) in branches]
+    return Bsz, N, H, branches, offs
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_problem_with_small_row_groups_bf16(B, oracle, seed):
+    """Plans that pack several row groups into a tile (and, for single images, split the walks): out within the rounding
+    of its bf16 result and of its numerators, lse within the row's bar; every seventh problem at scale = 1."""
+    Bsz, N, H, branches, offs = _small_group_problem(seed)
+    scale = 1.0 if seed % 7 == 0 else 0.125
+    plan = B.plan_describe_forward(Bsz, H, N, branches, offs)
+    packed = bool((plan["block_mult"] == 0).any())
+    split = B.workspace_bytes(Bsz, H, N, 64, B.DFA_BF16, branches, offs) > 0
+    print(f"[small groups {seed}] B={Bsz} N={N} H={H} branches={branches} offsets={offs} scale={scale} packed={packed} split={split}", flush=True)
+    (q, k, v), ex = make_qkv(4000 + seed, Bsz, N, H, 64, "bf16")
+    out, lse = B.forward(q, k, v, branches, scale, head_offsets=offs)
+    o_ref, l_ref = oracle.forward(*ex, branches, scale, head_offsets=offs)
+    check_lse_bf16(to_f64(lse), oracle, ex, branches, scale, l_ref, offs)
+    d = np.abs(to_f64(out) - o_ref)
+    assert np.all(d <= 2.0 ** -7 * np.maximum(1.0, np.abs(o_ref)))
+    assert np.all(to_f64(out)[np.isneginf(l_ref).transpose(0, 2, 1)] == 0.0)
+
+
 @pytest.mark.parametrize("seed", [3, 17, 22, 41, 59])
 def test_random_problem_with_sharp_softmax_bf16(B, oracle, seed):
     """scale = 1 (Eq. 2 as printed): scores of standard deviation 8, so one or two keys carry most rows.  That is
