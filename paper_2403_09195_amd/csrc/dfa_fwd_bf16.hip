@@ -287,7 +287,8 @@ __device__ __forceinline__ void settle(const floatx16 (&s_cur)[2], u32x4 (&p_cur
 
 // kSplit: the workgroup walks only its share of the tile's steps (see FwdParams::split_wgs) and leaves a partial
 // result (rows in tile order: out normalised, divided by the row's largest magnitude and rounded to fp16; lse and
-// those row scales in fp32) in its own block of the workspace; OutT is not used then.
+// those row scales in fp32) in its own block of the workspace; a tile that the launch leaves whole (one part) is
+// written out as in any other launch.  OutT is bf16 then.
 // kPacked: the plan has tiles that pack several row groups (multiplicities per 32-row block, filler slots); plans
 // without such tiles run the variant that has none of that in its way.
 template <typename OutT, bool kSplit, bool kPacked>
@@ -374,8 +375,10 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
     char* const blk = kSplit ? reinterpret_cast<char*>(p.split_ws) + (int64_t)blockIdx.x * kSplitBlockBytes : nullptr;
     float* const blk_lse = reinterpret_cast<float*>(blk + kTileRows * kD * 2);
     float* const blk_scale = blk_lse + kTileRows;
+    // a tile that the split launch walks whole (one part) is finished here like in any other launch
+    const bool partial = kSplit && nparts > 1;
 
-    if (kSplit && tile.nseg == 0) {
+    if (partial && tile.nseg == 0) {
         blk_lse[tid] = -INFINITY;     // the merge writes the zero rows
         return;
     }
@@ -615,13 +618,13 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
         inv[qb] = 1.0f / l_tot;
         const float ref = !kPacked ? m_ref[qb] + bias_cur : bias_q[qb] > -INFINITY ? m_ref[qb] + bias_q[qb] : m_kept[qb];
         const float lse_row = (ref + __builtin_amdgcn_logf(l_tot)) * kLn2;
-        if (kSplit) {
+        if (partial) {
             if (g_e == 0) blk_lse[slot] = slot < tile.nrows ? lse_row : -INFINITY;
         } else if (lse_out && g_e == 0 && slot < tile.nrows && (!kPacked || row_idx[slot] >= 0)) {
             lse_out[((int64_t)b * p.H + h) * p.N + row_idx[slot]] = lse_row;
         }
     }
-    if constexpr (kSplit) {
+    if (partial) {
         // Partial rows leave as fp16, each divided by its largest magnitude (kept in fp32 beside the row's lse): half
         // the bytes of fp32 rows, which is what a split launch is short of, at an error of 2^-12 of the row's largest
         // value per element.  Same detour through LDS as for bf16 rows below: whole 128-byte lines.
@@ -721,7 +724,7 @@ void dfa_fwd_bf16_kernel(const FwdParams p) {
 __global__ __launch_bounds__(256) void merge_split_kernel(const FwdParams p) {
     const ItemParts ip = p.item_parts[blockIdx.x];
     const Item item = p.items[blockIdx.x];
-    if (ip.nparts == 0) return;         // padding item
+    if (ip.nparts <= 1) return;         // padding item, or a tile walked whole (its workgroup wrote the rows itself)
     const int r = blockIdx.y * 32 + (threadIdx.x >> 3), sub = threadIdx.x & 7;
     const char* blk0 = reinterpret_cast<const char*>(p.split_ws) + (int64_t)ip.first_wg * kSplitBlockBytes;
     float lb[kMaxSplit];
@@ -791,9 +794,9 @@ hipError_t launch_fwd_bf16(const FwdParams& p, int n_items, bool out_f32, bool p
 // that launch_merge_split combines.
 hipError_t launch_fwd_bf16_split(const FwdParams& p, int n_split_wgs, bool packed, hipStream_t st) {
     if (packed)
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, true>), dim3(n_split_wgs), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<float, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((dfa_fwd_bf16_kernel<__bf16, true, false>), dim3(n_split_wgs), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

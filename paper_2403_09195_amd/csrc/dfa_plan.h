@@ -101,7 +101,10 @@ void build_plan(int32_t B, int32_t H, int32_t N, const dfa_branch_t* br, int32_t
 // Launches of the bf16 forward kernel with fewer workgroups than half the chip's slots are as long as their longest
 // tile's walk.  There the walks are cut: every tile gets one workgroup, then the workgroup slots left over go one by
 // one to the tile whose shares are longest (up to kMaxSplit shares, none shorter than kMinShareSteps), and a second,
-// small launch merges the partial results by their log-sum-exp weights.  Fills plan->split_wgs / item_parts, or
+// small launch merges the partial results of the tiles that were cut by their log-sum-exp weights (a tile left whole
+// is written out by its one workgroup).  Launches that fill more than half the slots are left alone: cutting their
+// longest walks fills every CU with two workgroups, which slows every step by more than the shorter walks save
+// (two 1024^2 images: 54.7 us against 46.1 us).  Fills plan->split_wgs / item_parts, or
 // leaves them empty when the launch is not to be split.
 void split_plan(HostPlan* plan, const ChipShape& chip);
 
